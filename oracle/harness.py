@@ -1,0 +1,71 @@
+"""Glue between the seeded input recipes and the CPU oracle.  TEST INFRASTRUCTURE ONLY.
+
+Builds oracle configs, float64 weights and the oracle's paged K/V pool from a `focus_inputs.Workload`.
+The same recipes feed the HIP library in the GPU tests, so both sides see identical bits.
+"""
+from __future__ import annotations
+
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+
+from focus_inputs import Workload
+from . import focus_oracle as fo
+
+
+def oracle_config(wl: Workload, **over) -> fo.OracleConfig:
+    cfg = fo.OracleConfig(
+        n_layers=wl.n_layers, hidden=wl.hidden, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads,
+        head_dim=wl.head_dim, ffn=wl.ffn, vocab=wl.vocab, block_size=wl.block_size,
+        mask_token_id=wl.mask_token_id, page_size=wl.page_size, rms_eps=wl.rms_eps, rope_base=wl.rope_base,
+        evict_layer=wl.evict_layer, importance_mode=wl.importance_mode, maxpool_k=wl.maxpool_k,
+        budget_mode=wl.budget_mode, topk=wl.topk, keep_ratio=wl.keep_ratio, alpha=wl.alpha,
+        constraints=wl.constraints, conf_threshold=wl.conf_threshold)
+    for k, v in over.items():
+        setattr(cfg, k, v)
+    return cfg
+
+
+def _f64(t) -> np.ndarray:
+    return t.to(dtype=__import__("torch").float64).numpy()
+
+
+def oracle_weights(wl: Workload, cache_layers: bool = True) -> fo.Weights:
+    """Float64 copies of the workload's weights (bf16 workloads: the bf16 bit patterns widened).
+    Layers are generated on first use; with cache_layers=False each fetch regenerates (large models)."""
+    cache: Dict[int, Dict[str, np.ndarray]] = {}
+    ones = np.ones(wl.hidden)
+
+    def layer(l: int):
+        if l in cache:
+            return cache[l]
+        w = {k: _f64(wl.layer_weight(l, k)) for k in ("w_qkv", "w_o", "w_gate_up", "w_down")}
+        w["attn_norm"] = ones
+        w["mlp_norm"] = ones
+        if cache_layers:
+            cache[l] = w
+        return w
+
+    return fo.Weights(_f64(wl.embed()), _f64(wl.lm_head()), ones, layer)
+
+
+def oracle_batch(wl: Workload, seq_ids: Optional[Sequence[int]] = None):
+    """Oracle pool + per-sequence states for the listed sequences of the workload's batch (default all),
+    with the prefix K/V in place: seeded synthetic pages, or a real prefill of the seeded prompts.
+    Returns (cfg, weights, pool, states, prefix_lens, page_tables, n_pages_total)."""
+    cfg = oracle_config(wl)
+    W = oracle_weights(wl, cache_layers=wl.n_layers <= 8)
+    lens = wl.prefix_lens()
+    tables, n_pages = wl.page_tables(lens)
+    ids = list(range(wl.batch)) if seq_ids is None else list(seq_ids)
+    pool = fo.KVPool(cfg)
+    states = [fo.new_seq_state(cfg, lens[b], tables[b]) for b in ids]
+    if wl.prefill == "synthetic":
+        for l in range(wl.n_layers):
+            for b in ids:
+                for pid in tables[b]:
+                    pool.layers[l][pid] = _f64(wl.kv_page(l, pid, n_pages))
+    else:
+        prompts = wl.prompt_tokens(lens)
+        fo.prefill(cfg, W, pool, states, [prompts[b] for b in ids])
+    return cfg, W, pool, states, lens, tables, n_pages
