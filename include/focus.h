@@ -1,0 +1,188 @@
+/*
+ * focus.h - C ABI of the MI355X (gfx950) FOCUS decode-step library.
+ *
+ * One call of focus_step() is one inference step of FOCUS (arXiv 2601.23278, Algorithm 1) for a batch
+ * of block-diffusion sequences that share one model: the whole block of B tokens runs through the layers
+ * up to the eviction layer e, the token importance (Eq. 2) of layers e-1 and e gives the importance
+ * delta (Eq. 3), a per-sequence budget K (Eq. 4-5, or a fixed budget) and the top-K / structural
+ * constraints of Sec. 4.2 pick the retained positions, the retained rows of all sequences are packed
+ * into one ragged batch, the rest of layer e and all later layers run on the packed rows only, and the
+ * confidence-based decoding commits tokens and updates the running statistics of App. E.3.1.
+ *
+ * Conventions
+ *   - Every function returns FOCUS_OK (0) or a negative FOCUS_E* code; focus_last_error() gives the text.
+ *     Nothing throws, nothing aborts.
+ *   - "device" pointers are HIP device memory of the current device, "host" pointers ordinary memory.
+ *   - Weights, the K/V pool and the workspace are BORROWED: the caller allocates them, keeps them alive
+ *     until focus_free(), and must not touch the workspace in between.
+ *   - focus_step / focus_select_compact / focus_commit only enqueue work on the given stream: no allocation,
+ *     no host synchronisation; outputs are valid once the caller has synchronised the stream.
+ *   - A context is not thread-safe.  The same calls on the same inputs give bitwise identical results
+ *     (no floating-point atomics anywhere).
+ *
+ * Layouts
+ *   - Matrices are row-major [out_features, in_features]; element type per focus_config.dtype.
+ *   - w_qkv rows: H_q*D query rows, then H_kv*D key rows, then H_kv*D value rows.
+ *     w_gate_up rows: F gate rows, then F up rows.
+ *   - K/V pool: [n_layers][n_pages][2 (K,V)][H_kv][page_size][D], element type per dtype.  K is stored
+ *     after the rotary embedding.  A sequence's token t lives in page page_table[t / page_size] at row
+ *     t % page_size; the current block occupies tokens prefix_len .. prefix_len + B - 1.
+ *   - Bit sets over block positions are uint64_t, bit p = position p (B <= 64).
+ *   - Packed rows: sequences in batch order, positions ascending; row_map[r] = b * B + p.
+ */
+#ifndef FOCUS_H
+#define FOCUS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FOCUS_MAX_BLOCK 64
+
+enum { FOCUS_OK = 0, FOCUS_EINVAL = -1, FOCUS_ENOMEM = -2, FOCUS_EHIP = -3 };
+enum { FOCUS_F32 = 0, FOCUS_BF16 = 1 };
+enum { FOCUS_BUDGET_TOPK = 0, FOCUS_BUDGET_RATIO = 1, FOCUS_BUDGET_DYNAMIC = 2, FOCUS_BUDGET_OVERRIDE = 3 };
+enum { FOCUS_KEEP_AR_CONTEXT = 1, FOCUS_KEEP_PLACEHOLDERS = 2 };
+
+typedef struct focus_ctx focus_ctx;
+
+/* Plain data, copied by focus_init. */
+typedef struct focus_config {
+  int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
+  int32_t dtype;            /* FOCUS_F32 or FOCUS_BF16: weights, activations and K/V; the residual stream,
+                               softmax, importance and logits are fp32 in both */
+  float   rms_eps;
+  float   rope_base;        /* rotate-half pairing (i, i + D/2), angle pos * base^(-2i/D) */
+  int32_t block_size;       /* B, 1..64 */
+  int32_t mask_token_id;
+  int32_t max_batch;        /* number of sequence slots */
+  int32_t max_prefix_len;   /* longest prefix any slot will hold */
+  int32_t page_size;        /* tokens per K/V page */
+  int32_t n_pages;          /* pages per layer in the K/V pool */
+  int32_t evict_layer;      /* e (Alg. 1 uses 1); 1 <= e < n_layers when importance_mode is 0 */
+  int32_t importance_mode;  /* 0: delta I(e) - I(e-1) (Eq. 3); 1: raw I(e) */
+  int32_t maxpool_k;        /* MaxPool1D window of Eq. 2: 3 (App. F.1) or 1 (off) */
+  int32_t budget_mode;      /* FOCUS_BUDGET_* */
+  int32_t topk;             /* FOCUS_BUDGET_TOPK */
+  float   keep_ratio;       /* FOCUS_BUDGET_RATIO: K = ceil(keep_ratio * B) */
+  float   alpha;            /* FOCUS_BUDGET_DYNAMIC: expansion factor of Eq. 4 */
+  int32_t constraints;      /* FOCUS_KEEP_* bits (Sec. 4.2) */
+  float   conf_threshold;   /* commit when confidence >= threshold */
+} focus_config;
+
+/* Device pointers.  The per-layer members are HOST arrays of n_layers device pointers. */
+typedef struct focus_weights {
+  const void *embed;        /* [vocab, hidden] */
+  const void *lm_head;      /* [vocab, hidden] */
+  const void *final_norm;   /* [hidden] */
+  const void *const *attn_norm;   /* [hidden] */
+  const void *const *w_qkv;       /* [(H_q + 2 H_kv) D, hidden] */
+  const void *const *w_o;         /* [hidden, H_q D] */
+  const void *const *mlp_norm;    /* [hidden] */
+  const void *const *w_gate_up;   /* [2 F, hidden] */
+  const void *const *w_down;      /* [hidden, F] */
+} focus_weights;
+
+/* Optional outputs of a step; every member is a caller-allocated device pointer or NULL.  n = n_seq,
+ * T' = cu_seqlens[n] <= n * B. */
+typedef struct focus_step_out {
+  int32_t  *tokens;         /* [n, B]   block token ids after the commit (mask id where still masked) */
+  uint64_t *mask_bits;      /* [n]      still-masked positions after the commit */
+  int32_t  *n_decoded;      /* [n]      tokens unmasked by this step */
+  float    *importance_prev;/* [n, B]   Eq. 2 at layer e-1 (importance_mode 0) */
+  float    *importance;     /* [n, B]   Eq. 2 at layer e */
+  float    *delta_I;        /* [n, B]   Eq. 3 */
+  int32_t  *K;              /* [n]      budget */
+  uint64_t *keep_bits;      /* [n]      retained set S */
+  int32_t  *cu_seqlens;     /* [n + 1]  exclusive prefix sum of |S| */
+  int32_t  *row_map;        /* [n * B]  first T' entries valid */
+  float    *conf;           /* [n * B]  first T' entries valid: probability of the arg-max token */
+  int32_t  *argmax;         /* [n * B]  first T' entries valid */
+  float    *hidden_full;    /* [n * B, hidden]  residual stream entering layer e */
+  float    *hidden_packed;  /* [n * B, hidden]  first T' rows valid: residual stream after the last layer */
+  float    *logits;         /* [n * B, vocab]   first T' rows valid */
+} focus_step_out;
+
+/* Host copy of one slot's block state (App. E.3.1 plus the block's tokens). */
+typedef struct focus_seq_state {
+  int32_t  prefix_len;
+  int32_t  total_steps;
+  int64_t  token_sum;
+  uint64_t mask_bits;
+  uint64_t processed_bits;  /* positions that have K/V in the layers above e */
+  int32_t  tokens[FOCUS_MAX_BLOCK];
+} focus_seq_state;
+
+/* Sizes the caller must allocate.  Both need only the shape members of cfg. */
+int focus_workspace_bytes(const focus_config *cfg, size_t *bytes);
+int focus_kv_pool_bytes(const focus_config *cfg, size_t *bytes);
+
+/* Creates a context over borrowed device memory.  Builds the rotary table and zeroes the slot state
+ * (synchronous).  EINVAL: bad shape / unsupported switch / NULL; ENOMEM: a buffer is too small. */
+int focus_init(const focus_config *cfg, const focus_weights *weights, void *kv_pool, size_t kv_pool_bytes,
+               void *workspace, size_t workspace_bytes, focus_ctx **out);
+
+/* Installs n_seq sequences and resets their block state (all B positions masked, nothing processed; the
+ * running statistics are reset too unless keep_stats != 0, App. E.3.1 "state persistence").
+ *   seq_slot      host [n_seq] slot of each sequence, or NULL for 0..n_seq-1
+ *   prefix_len    host [n_seq]
+ *   page_table    host [n_seq, table_stride]: physical pages covering prefix_len + B tokens
+ *   prompt_tokens host, the prompts concatenated in order (sum of prefix_len ids), or NULL.
+ *                 Not NULL: computes the exact prefix K/V of every layer (the prompt is cut into blocks of
+ *                 B tokens, each attends to all earlier blocks and bidirectionally to itself; Sec. 2).
+ *                 NULL: the pool already holds the prefix K/V (e.g. seeded synthetic pages).
+ * Synchronises the stream before returning. */
+int focus_prefill_kv(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32_t *seq_slot,
+                     const int32_t *prefix_len, const int32_t *page_table, int32_t table_stride,
+                     const int32_t *prompt_tokens, int32_t keep_stats);
+
+/* One FOCUS step (Algorithm 1) for sequences seq_slot[0..n_seq) in that batch order.
+ *   seq_slot      device [n_seq] or NULL for slots 0..n_seq-1
+ *   k_override    device [n_seq] budgets for FOCUS_BUDGET_OVERRIDE, else NULL
+ *   keep_override device [n_seq] retained sets to use instead of budget + selection, or NULL
+ *   out           host struct of device pointers, or NULL */
+int focus_step(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32_t *seq_slot,
+               const int32_t *k_override, const uint64_t *keep_override, const focus_step_out *out);
+
+/* Stage entry: budget (Eq. 4-5), selection (Alg. 1 phase 3) and packing on caller-given scores, using the
+ * slots' current mask bits and statistics.  Writes out->K, keep_bits, cu_seqlens, row_map.  Does not change
+ * the slot state.
+ *   delta_I       device [n_seq, B] fp32 */
+int focus_select_compact(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32_t *seq_slot,
+                         const float *delta_I, const int32_t *k_override, const focus_step_out *out);
+
+/* Stage entry: confidence-based commit (Alg. 1 Decode_and_Verify, App. E.3.1 statistics) on caller-given
+ * confidences.  Updates the slot state and writes out->tokens, mask_bits, n_decoded.
+ *   keep_bits     device [n_seq]; cu_seqlens device [n_seq + 1]; conf, argmax device [cu_seqlens[n_seq]] */
+int focus_commit(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32_t *seq_slot,
+                 const uint64_t *keep_bits, const int32_t *cu_seqlens, const float *conf,
+                 const int32_t *argmax, const focus_step_out *out);
+
+/* Debug access to one slot's state (synchronous device copies). */
+int focus_get_state(focus_ctx *ctx, int32_t slot, focus_seq_state *state);
+int focus_set_state(focus_ctx *ctx, int32_t slot, const focus_seq_state *state);
+
+/* Per-kernel-class device time of the last focus_step.  With timing enabled every kernel launch of a step
+ * is bracketed by a pair of HIP events on the step's stream (this adds small gaps between kernels, so time
+ * whole steps with timing off).  focus_get_kernel_time synchronises the stream and returns the summed
+ * duration and the number of launches of one class. */
+enum { FOCUS_KC_GEMM = 0,      /* dense projections: QKV, O, gate/up, down, lm_head */
+       FOCUS_KC_ATTENTION = 1, /* block attention over the paged K/V */
+       FOCUS_KC_EVICT = 2,     /* importance, budget + selection, scan, gather */
+       FOCUS_KC_POINTWISE = 3, /* embedding, RMSNorm, rotary + K/V write, SiLU*up */
+       FOCUS_KC_DECODE = 4,    /* confidence over the vocabulary, commit */
+       FOCUS_KC_COUNT = 5 };
+int focus_set_timing(focus_ctx *ctx, int32_t enable);
+int focus_get_kernel_time(focus_ctx *ctx, int32_t kernel_class, float *total_ms, int32_t *launches);
+
+int focus_free(focus_ctx *ctx);
+/* Text of the last error of ctx, or of the last failed call without a context when ctx is NULL. */
+const char *focus_last_error(const focus_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FOCUS_H */

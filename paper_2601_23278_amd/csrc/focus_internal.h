@@ -1,0 +1,121 @@
+// Internal declarations shared by the translation units of libfocus: the context, the workspace
+// plan and the host-side launch wrappers of every kernel.  Nothing here is part of the C ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string>
+#include <vector>
+
+#include "focus.h"
+
+typedef __bf16 bf16_t;
+
+namespace fk {
+
+// Number of valid rows of a launch: the grid is sized for `cap` rows; kernels read the actual count
+// from `count` (device memory, written earlier on the same stream) when it is not null.
+struct Rows {
+  int cap;
+  const int32_t *count;
+};
+
+// Device arrays indexed by sequence slot.
+struct SlotState {
+  int32_t *prefix_len;
+  int32_t *page_table;    // [max_batch, table_stride]
+  int32_t table_stride;
+  int32_t *tokens;        // [max_batch, B]
+  uint64_t *mask_bits;
+  uint64_t *processed_bits;
+  int64_t *token_sum;
+  int32_t *total_steps;
+  int32_t max_batch;
+};
+
+// Slot of batch entry b.  A caller-supplied slot list lives in device memory and cannot be checked on the
+// host, so it is clamped into range here: a bad entry aliases another slot instead of leaving the workspace.
+__device__ __forceinline__ int slot_of(const int32_t *seq_slot, int b, const SlotState &st) {
+  if (!seq_slot) return b;
+  int s = seq_slot[b];
+  return s < 0 ? 0 : (s >= st.max_batch ? st.max_batch - 1 : s);
+}
+
+// How a kernel maps a row to its sequence: row_map[r] = b * B + p, slot = seq_slot ? seq_slot[b] : b.
+struct RowIndex {
+  const int32_t *row_map;
+  const int32_t *seq_slot;
+  int B;
+};
+
+// Geometry of the paged K/V pool for one layer.
+struct KvLayer {
+  void *base;             // start of this layer's pages
+  int page_size, n_kv_heads, head_dim;
+};
+
+enum Epilogue { EPI_STORE = 0 /* out[dtype] = acc */, EPI_ADD_F32 = 1 /* out[f32] += acc */, EPI_STORE_F32 = 2 };
+
+void embed(hipStream_t s, int dtype, const void *table, int hidden, Rows rows, RowIndex ri, SlotState st,
+           int mask_id, float *resid);
+void rmsnorm(hipStream_t s, int dtype, const float *x, const void *w, void *y, int hidden, float eps, Rows rows);
+void gemm(hipStream_t s, int dtype, const void *A, const void *W, int N, int K, Rows rows, int epilogue,
+          void *out, int ldo);
+// Rotates q and k rows of the fused qkv buffer in place and stores k, v of every row into its cache slot.
+void rope_kv_write(hipStream_t s, int dtype, void *qkv, int n_q_heads, Rows rows, RowIndex ri, SlotState st,
+                   KvLayer kv, const float2 *rope_table);
+void attention(hipStream_t s, int dtype, const void *q, int q_stride, int n_q_heads, Rows rows, RowIndex ri,
+               SlotState st, const uint64_t *vis_by_b, KvLayer kv, void *out);
+// Eq. 2 per (sequence, query head) on the full-block qkv buffer: partial[b, h, j].
+void importance(hipStream_t s, int dtype, const void *qkv, int n_seq, int B, int n_q_heads, int n_kv_heads,
+                int head_dim, int maxpool_k, float *partial);
+struct SelectArgs {
+  int n_seq, B, n_q_heads;
+  const float *partial_prev, *partial_evict;   // [n, Hq, B] or null (then delta_in is used)
+  const float *delta_in;                       // [n, B] or null
+  int importance_mode, budget_mode, K_fixed, constraints;
+  float alpha;
+  const int32_t *k_override;
+  const uint64_t *keep_override;
+  const int32_t *seq_slot;
+  SlotState st;
+  int update_state;                            // processed_bits |= keep
+  float *imp_prev_out, *imp_out, *delta_out;   // [n, B] or null
+  int32_t *K_out;
+  uint64_t *keep_out;
+  int32_t *n_keep_out;
+  uint64_t *vis_out;                           // [n] processed bits after the update, by batch index
+};
+void select(hipStream_t s, const SelectArgs &a);
+// cu[b] = exclusive prefix sum of n_keep, row_map, cu[n] also to *total.
+void scan_compact(hipStream_t s, int n_seq, int B, const uint64_t *keep_bits, int32_t *cu, int32_t *row_map,
+                  int32_t *total);
+void gather_rows(hipStream_t s, int dtype, Rows rows, const int32_t *row_map, const float *resid, float *resid_p,
+                 int hidden, const void *qkv, int qkv_stride, void *q_p, int q_width);
+void silu_mul(hipStream_t s, int dtype, const void *gate_up, void *act, int ffn, Rows rows);
+void confidence(hipStream_t s, const float *logits, int vocab, Rows rows, float *conf, int32_t *argmax);
+struct CommitArgs {
+  int n_seq, B;
+  const int32_t *seq_slot;
+  SlotState st;
+  const uint64_t *keep_bits;
+  const int32_t *cu;
+  const float *conf;
+  const int32_t *argmax;
+  float threshold;
+  int mask_id;
+  int32_t *tokens_out;       // [n, B] or null
+  uint64_t *mask_out;
+  int32_t *n_decoded_out;
+};
+void commit(hipStream_t s, const CommitArgs &a);
+// Prefill helper: installs chunk c of every prompt as the block (unmasked tokens, prefix_len = c * B).
+void prefill_chunk_setup(hipStream_t s, int n_seq, int B, int chunk, const int32_t *seq_slot, SlotState st,
+                         const int32_t *prompt, const int32_t *prompt_offset, const int32_t *prompt_len,
+                         uint64_t *keep_bits);
+void reset_block_state(hipStream_t s, int n_seq, int B, const int32_t *seq_slot, SlotState st,
+                       const int32_t *prefix_len, int mask_id, int keep_stats);
+void fill_u64(hipStream_t s, uint64_t *p, int n, uint64_t v);
+void iota_rows(hipStream_t s, int32_t *row_map, int32_t *cu, int n_seq, int B, int32_t *total);
+
+}  // namespace fk

@@ -1,0 +1,240 @@
+// Row-wise and element-wise kernels of the decode step: embedding lookup, RMSNorm, rotary embedding fused
+// with the K/V cache write, row gather for the packed batch, SiLU(gate)*up, and small state set-up kernels.
+// All are bandwidth-bound; one workgroup handles one row with 16-byte accesses where the layout allows.
+#include "focus_internal.h"
+
+namespace fk {
+
+template <typename T> __device__ __forceinline__ float to_f(T v) { return (float)v; }
+template <typename T> __device__ __forceinline__ T from_f(float v) { return (T)v; }
+
+__device__ __forceinline__ int n_rows(Rows r) { return r.count ? min(*r.count, r.cap) : r.cap; }
+
+__device__ __forceinline__ float block_sum_256(float v, float *sh) {
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  int w = threadIdx.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sh[w] = v;
+  __syncthreads();
+  return sh[0] + sh[1] + sh[2] + sh[3];
+}
+
+// ---------------------------------------------------------------------------------------------
+// Block input (Alg. 1 "Masked Block X"): mask embedding where masked, committed token's embedding elsewhere.
+template <typename T>
+__global__ __launch_bounds__(256) void k_embed(const T *table, int hidden, Rows rows, RowIndex ri, SlotState st,
+                                               int mask_id, float *resid) {
+  int r = blockIdx.x;
+  if (r >= n_rows(rows)) return;
+  int rm = ri.row_map[r], b = rm / ri.B, p = rm % ri.B;
+  int slot = slot_of(ri.seq_slot, b, st);
+  int tok = ((st.mask_bits[slot] >> p) & 1ull) ? mask_id : st.tokens[slot * ri.B + p];
+  const T *src = table + (size_t)tok * hidden;
+  float *dst = resid + (size_t)r * hidden;
+  for (int i = threadIdx.x; i < hidden; i += 256) dst[i] = to_f(src[i]);
+}
+
+void embed(hipStream_t s, int dtype, const void *table, int hidden, Rows rows, RowIndex ri, SlotState st,
+           int mask_id, float *resid) {
+  if (rows.cap <= 0) return;
+  if (dtype == FOCUS_F32)
+    k_embed<float><<<rows.cap, 256, 0, s>>>((const float *)table, hidden, rows, ri, st, mask_id, resid);
+  else
+    k_embed<bf16_t><<<rows.cap, 256, 0, s>>>((const bf16_t *)table, hidden, rows, ri, st, mask_id, resid);
+}
+
+// ---------------------------------------------------------------------------------------------
+// y = x / sqrt(mean(x^2) + eps) * w, x fp32 residual stream, y in the activation type.
+template <typename T>
+__global__ __launch_bounds__(256) void k_rmsnorm(const float *x, const T *w, T *y, int hidden, float eps, Rows rows) {
+  __shared__ float sh[4];
+  int r = blockIdx.x;
+  if (r >= n_rows(rows)) return;
+  const float *xr = x + (size_t)r * hidden;
+  float ss = 0.f;
+  for (int i = threadIdx.x * 4; i < hidden; i += 1024) {
+    float4 v = *(const float4 *)(xr + i);
+    ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+  }
+  ss = block_sum_256(ss, sh);
+  float inv = 1.0f / sqrtf(ss / (float)hidden + eps);
+  T *yr = y + (size_t)r * hidden;
+  for (int i = threadIdx.x * 4; i < hidden; i += 1024) {
+    float4 v = *(const float4 *)(xr + i);
+    yr[i + 0] = from_f<T>(v.x * inv * to_f(w[i + 0]));
+    yr[i + 1] = from_f<T>(v.y * inv * to_f(w[i + 1]));
+    yr[i + 2] = from_f<T>(v.z * inv * to_f(w[i + 2]));
+    yr[i + 3] = from_f<T>(v.w * inv * to_f(w[i + 3]));
+  }
+}
+
+void rmsnorm(hipStream_t s, int dtype, const float *x, const void *w, void *y, int hidden, float eps, Rows rows) {
+  if (rows.cap <= 0) return;
+  if (dtype == FOCUS_F32)
+    k_rmsnorm<float><<<rows.cap, 256, 0, s>>>(x, (const float *)w, (float *)y, hidden, eps, rows);
+  else
+    k_rmsnorm<bf16_t><<<rows.cap, 256, 0, s>>>(x, (const bf16_t *)w, (bf16_t *)y, hidden, eps, rows);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Rotary embedding (rotate-half) of the q and k heads of one row, in place, and the K/V cache write of the
+// row's k (rotated) and v into the slot of its absolute position (App. C: the K/V of a layer is filled for
+// every row that enters the layer, before anything is evicted).
+template <typename T>
+__global__ __launch_bounds__(256) void k_rope_kv_write(T *qkv, int Hq, Rows rows, RowIndex ri, SlotState st, KvLayer kv,
+                                                       const float2 *rope) {
+  int r = blockIdx.x;
+  if (r >= n_rows(rows)) return;
+  const int D = kv.head_dim, half = D / 2, Hkv = kv.n_kv_heads, P = kv.page_size;
+  int rm = ri.row_map[r], b = rm / ri.B, p = rm % ri.B;
+  int slot = slot_of(ri.seq_slot, b, st);
+  int pos = st.prefix_len[slot] + p;
+  int page = st.page_table[(size_t)slot * st.table_stride + pos / P], off = pos % P;
+  T *row = qkv + (size_t)r * (Hq + 2 * Hkv) * D;
+  T *cache = (T *)kv.base + (size_t)page * 2 * Hkv * P * D;
+  const float2 *cs = rope + (size_t)pos * half;
+  // q and k heads: one (head, pair) per thread step
+  for (int i = threadIdx.x; i < (Hq + Hkv) * half; i += 256) {
+    int h = i / half, d = i % half;
+    float2 c = cs[d];
+    float x1 = to_f(row[h * D + d]), x2 = to_f(row[h * D + d + half]);
+    T y1 = from_f<T>(x1 * c.x - x2 * c.y), y2 = from_f<T>(x2 * c.x + x1 * c.y);
+    row[h * D + d] = y1;
+    row[h * D + d + half] = y2;
+    if (h >= Hq) {
+      T *dst = cache + ((size_t)(h - Hq) * P + off) * D;
+      dst[d] = y1;
+      dst[d + half] = y2;
+    }
+  }
+  const T *v = row + (size_t)(Hq + Hkv) * D;
+  T *vc = cache + (size_t)Hkv * P * D;
+  for (int i = threadIdx.x; i < Hkv * D; i += 256) {
+    int h = i / D, d = i % D;
+    vc[((size_t)h * P + off) * D + d] = v[i];
+  }
+}
+
+void rope_kv_write(hipStream_t s, int dtype, void *qkv, int n_q_heads, Rows rows, RowIndex ri, SlotState st,
+                   KvLayer kv, const float2 *rope_table) {
+  if (rows.cap <= 0) return;
+  if (dtype == FOCUS_F32)
+    k_rope_kv_write<float><<<rows.cap, 256, 0, s>>>((float *)qkv, n_q_heads, rows, ri, st, kv, rope_table);
+  else
+    k_rope_kv_write<bf16_t><<<rows.cap, 256, 0, s>>>((bf16_t *)qkv, n_q_heads, rows, ri, st, kv, rope_table);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Gather of the retained rows (Sec. 4.2): residual stream and the layer-e queries, into packed order.
+template <typename T>
+__global__ __launch_bounds__(256) void k_gather(Rows rows, const int32_t *row_map, const float *resid, float *resid_p,
+                                                int hidden, const T *qkv, int qkv_stride, T *q_p, int q_width) {
+  int r = blockIdx.x;
+  if (r >= n_rows(rows)) return;
+  int src = row_map[r];
+  const float4 *a = (const float4 *)(resid + (size_t)src * hidden);
+  float4 *o = (float4 *)(resid_p + (size_t)r * hidden);
+  for (int i = threadIdx.x; i < hidden / 4; i += 256) o[i] = a[i];
+  const T *q = qkv + (size_t)src * qkv_stride;
+  T *qo = q_p + (size_t)r * q_width;
+  for (int i = threadIdx.x; i < q_width; i += 256) qo[i] = q[i];
+}
+
+void gather_rows(hipStream_t s, int dtype, Rows rows, const int32_t *row_map, const float *resid, float *resid_p,
+                 int hidden, const void *qkv, int qkv_stride, void *q_p, int q_width) {
+  if (rows.cap <= 0) return;
+  if (dtype == FOCUS_F32)
+    k_gather<float><<<rows.cap, 256, 0, s>>>(rows, row_map, resid, resid_p, hidden, (const float *)qkv, qkv_stride,
+                                             (float *)q_p, q_width);
+  else
+    k_gather<bf16_t><<<rows.cap, 256, 0, s>>>(rows, row_map, resid, resid_p, hidden, (const bf16_t *)qkv, qkv_stride,
+                                              (bf16_t *)q_p, q_width);
+}
+
+// ---------------------------------------------------------------------------------------------
+// act = silu(gate) * up over the fused [rows, 2F] projection.
+template <typename T>
+__global__ __launch_bounds__(256) void k_silu_mul(const T *gu, T *act, int ffn, Rows rows) {
+  int r = blockIdx.y;
+  if (r >= n_rows(rows)) return;
+  int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= ffn) return;
+  float g = to_f(gu[(size_t)r * 2 * ffn + i]), u = to_f(gu[(size_t)r * 2 * ffn + ffn + i]);
+  act[(size_t)r * ffn + i] = from_f<T>(g / (1.0f + __expf(-g)) * u);
+}
+
+void silu_mul(hipStream_t s, int dtype, const void *gate_up, void *act, int ffn, Rows rows) {
+  if (rows.cap <= 0) return;
+  dim3 grid((ffn + 255) / 256, rows.cap);
+  if (dtype == FOCUS_F32)
+    k_silu_mul<float><<<grid, 256, 0, s>>>((const float *)gate_up, (float *)act, ffn, rows);
+  else
+    k_silu_mul<bf16_t><<<grid, 256, 0, s>>>((const bf16_t *)gate_up, (bf16_t *)act, ffn, rows);
+}
+
+// ---------------------------------------------------------------------------------------------
+// state set-up
+
+__global__ void k_fill_u64(uint64_t *p, int n, uint64_t v) {
+  int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+void fill_u64(hipStream_t s, uint64_t *p, int n, uint64_t v) {
+  if (n > 0) k_fill_u64<<<(n + 255) / 256, 256, 0, s>>>(p, n, v);
+}
+
+// Row map of the full (not yet evicted) batch: row r is (b, p) = (r / B, r % B); cu[b] = b * B.
+__global__ void k_iota_rows(int32_t *row_map, int32_t *cu, int n_seq, int B, int32_t *total) {
+  int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n_seq * B) row_map[i] = i;
+  if (i <= n_seq) cu[i] = i * B;
+  if (i == 0) *total = n_seq * B;
+}
+void iota_rows(hipStream_t s, int32_t *row_map, int32_t *cu, int n_seq, int B, int32_t *total) {
+  k_iota_rows<<<(n_seq * B + 256) / 256, 256, 0, s>>>(row_map, cu, n_seq, B, total);
+}
+
+// New block: every position masked, nothing processed; statistics kept or cleared.
+__global__ void k_reset_block(int n_seq, int B, const int32_t *seq_slot, SlotState st, const int32_t *prefix_len,
+                              int mask_id, int keep_stats) {
+  int b = blockIdx.x;
+  int slot = slot_of(seq_slot, b, st);
+  if (threadIdx.x < B) st.tokens[slot * B + threadIdx.x] = mask_id;
+  if (threadIdx.x == 0) {
+    st.prefix_len[slot] = prefix_len[b];
+    st.mask_bits[slot] = B >= 64 ? ~0ull : ((1ull << B) - 1);
+    st.processed_bits[slot] = 0;
+    if (!keep_stats) {
+      st.token_sum[slot] = 0;
+      st.total_steps[slot] = 0;
+    }
+  }
+}
+void reset_block_state(hipStream_t s, int n_seq, int B, const int32_t *seq_slot, SlotState st,
+                       const int32_t *prefix_len, int mask_id, int keep_stats) {
+  if (n_seq > 0) k_reset_block<<<n_seq, 64, 0, s>>>(n_seq, B, seq_slot, st, prefix_len, mask_id, keep_stats);
+}
+
+// Prefill: chunk c of each prompt becomes the (fully unmasked) block at prefix_len = c * B; sequences whose
+// prompt has ended contribute no rows.
+__global__ void k_prefill_chunk(int n_seq, int B, int chunk, const int32_t *seq_slot, SlotState st, const int32_t *prompt,
+                                const int32_t *prompt_offset, const int32_t *prompt_len, uint64_t *keep_bits) {
+  int b = blockIdx.x;
+  int slot = slot_of(seq_slot, b, st);
+  int start = chunk * B;
+  int nr = min(max(prompt_len[b] - start, 0), B);
+  if ((int)threadIdx.x < nr) st.tokens[slot * B + threadIdx.x] = prompt[prompt_offset[b] + start + threadIdx.x];
+  if (threadIdx.x == 0) {
+    st.prefix_len[slot] = start;
+    st.mask_bits[slot] = 0;
+    keep_bits[b] = nr >= 64 ? ~0ull : ((1ull << nr) - 1);
+  }
+}
+void prefill_chunk_setup(hipStream_t s, int n_seq, int B, int chunk, const int32_t *seq_slot, SlotState st,
+                         const int32_t *prompt, const int32_t *prompt_offset, const int32_t *prompt_len,
+                         uint64_t *keep_bits) {
+  if (n_seq > 0)
+    k_prefill_chunk<<<n_seq, 64, 0, s>>>(n_seq, B, chunk, seq_slot, st, prompt, prompt_offset, prompt_len, keep_bits);
+}
+
+}  // namespace fk

@@ -1,0 +1,84 @@
+"""CPU-side checks of the C ABI: the library loads, exports every function the header declares, the ctypes
+mirrors of the structs have the C layout, and argument errors are reported without touching a GPU."""
+import ctypes as C
+import os
+import re
+import subprocess
+import tempfile
+
+import pytest
+
+import focus_inputs as fi
+import paper_2601_23278_amd as pk
+from paper_2601_23278_amd import binding
+from paper_2601_23278_amd.runner import config_from_workload
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "focus.h")
+
+
+def declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(focus_[a-z_]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_function():
+    names = declared_functions()
+    assert {"focus_init", "focus_prefill_kv", "focus_step", "focus_free"} <= set(names)
+    lib = C.CDLL(binding.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(binding.EXPORTS) == names                 # the binding covers the same set
+
+
+def test_struct_layouts_match_the_header():
+    prog = r'''
+#include <stdio.h>
+#include <stddef.h>
+#include "focus.h"
+int main(void) {
+  printf("%zu %zu %zu %zu\n", sizeof(focus_config), sizeof(focus_weights), sizeof(focus_step_out), sizeof(focus_seq_state));
+  printf("%zu %zu %zu %zu\n", offsetof(focus_config, rms_eps), offsetof(focus_config, keep_ratio),
+         offsetof(focus_config, conf_threshold), offsetof(focus_seq_state, tokens));
+  printf("%zu %zu\n", offsetof(focus_step_out, logits), offsetof(focus_weights, w_down));
+  return 0;
+}'''
+    with tempfile.TemporaryDirectory() as d:
+        open(os.path.join(d, "t.c"), "w").write(prog)
+        subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"),
+                               os.path.join(d, "t.c"), "-o", os.path.join(d, "t")])
+        out = subprocess.check_output([os.path.join(d, "t")]).decode().split()
+    got = [int(x) for x in out]
+    exp = [C.sizeof(pk.focus_config), C.sizeof(binding.focus_weights), C.sizeof(pk.focus_step_out), C.sizeof(pk.focus_seq_state),
+           pk.focus_config.rms_eps.offset, pk.focus_config.keep_ratio.offset, pk.focus_config.conf_threshold.offset,
+           pk.focus_seq_state.tokens.offset, pk.focus_step_out.logits.offset, binding.focus_weights.w_down.offset]
+    assert got == exp
+
+
+def good_cfg():
+    return config_from_workload(fi.workload("c1_tiny"), 4, 64, 24)
+
+
+def test_sizes_and_config_errors_without_gpu():
+    c = good_cfg()
+    assert pk.focus_workspace_bytes(c) > 0
+    assert pk.focus_kv_pool_bytes(c) == 2 * 24 * 2 * 4 * 16 * 64 * 4
+    for field, bad in [("head_dim", 96), ("block_size", 65), ("block_size", 0), ("n_kv_heads", 3), ("dtype", 7),
+                       ("evict_layer", 0), ("evict_layer", 2), ("maxpool_k", 5), ("budget_mode", 4), ("constraints", 4),
+                       ("mask_token_id", 1024), ("hidden", 100), ("n_pages", 0)]:
+        c = good_cfg()
+        setattr(c, field, bad)
+        with pytest.raises(pk.FocusError) as e:
+            pk.focus_workspace_bytes(c)
+        assert e.value.code == binding.FOCUS_EINVAL, field
+
+
+def test_init_rejects_null_and_reports_text():
+    lib = binding._lib
+    ctx = C.c_void_p()
+    c = good_cfg()
+    rc = lib.focus_init(C.byref(c), None, None, 0, None, 0, C.byref(ctx))
+    assert rc == binding.FOCUS_EINVAL and b"null" in lib.focus_last_error(None)
+    assert lib.focus_step(None, None, 1, None, None, None, None) == binding.FOCUS_EINVAL
+    assert lib.focus_free(None) == binding.FOCUS_OK

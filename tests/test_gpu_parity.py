@@ -1,0 +1,351 @@
+"""Parity of the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
+
+Integer results (budget, retained sets, packing offsets, row map, committed ids, mask bits, counters) must be
+bit-exact given identical scores; floating point within max|gpu - oracle| / max|oracle| <= 1e-3 (fp32 model)
+or 2e-2 (bf16 model).  Where a bf16 score decides an integer, the GPU's decision is accepted only if it is a
+valid decision for the oracle's scores within that tolerance, and the oracle then continues from the GPU's
+decision (teacher forcing) so that later stages stay comparable.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import focus_inputs as fi
+from oracle import focus_oracle as fo
+from oracle.harness import oracle_batch, oracle_config
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def _pk():
+    import paper_2601_23278_amd as pk
+    from paper_2601_23278_amd import runner
+    return pk, runner
+
+
+def bits_of(positions):
+    v = 0
+    for p in positions:
+        v |= 1 << p
+    return v
+
+
+def positions_of(bits, B):
+    return [p for p in range(B) if (bits >> p) & 1]
+
+
+def relerr(gpu, ora):
+    ora = np.asarray(ora, dtype=np.float64)
+    gpu = np.asarray(gpu, dtype=np.float64)
+    if ora.size == 0:
+        return 0.0
+    return float(np.max(np.abs(gpu - ora)) / max(np.max(np.abs(ora)), 1e-30))
+
+
+def row_relerr(gpu, ora):
+    return max([relerr(g, o) for g, o in zip(gpu, ora)] + [0.0])
+
+
+class Outs:
+    def __init__(self, pk, wl, n):
+        B, h, V = wl.block_size, wl.hidden, wl.vocab
+        d = DEV
+        z = lambda *s, dt=torch.float32: torch.zeros(*s, dtype=dt, device=d)
+        self.t = dict(tokens=z(n, B, dt=torch.int32), mask_bits=z(n, dt=torch.int64), n_decoded=z(n, dt=torch.int32),
+                      importance_prev=z(n, B), importance=z(n, B), delta_I=z(n, B), K=z(n, dt=torch.int32),
+                      keep_bits=z(n, dt=torch.int64), cu_seqlens=z(n + 1, dt=torch.int32), row_map=z(n * B, dt=torch.int32),
+                      conf=z(n * B), argmax=z(n * B, dt=torch.int32), hidden_full=z(n * B, h), hidden_packed=z(n * B, h),
+                      logits=z(n * B, V))
+        self.struct = pk.make_step_out(**self.t)
+
+    def host(self):
+        torch.cuda.synchronize()
+        return {k: v.cpu().numpy() for k, v in self.t.items()}
+
+
+def u64(x):
+    return int(x) & ((1 << 64) - 1)
+
+
+def check_selection_valid(dI_ora, masked, keep_gpu, K, B, tol):
+    """The GPU's top-K is a valid top-K of the oracle's scores up to `tol`."""
+    cand = [j for j in range(B) if masked[j]]
+    k = min(K, len(cand))
+    if k == 0 or K >= B:
+        return
+    srt = sorted((dI_ora[j] for j in cand), reverse=True)
+    kth = srt[k - 1]
+    for j in cand:
+        if j in keep_gpu:
+            assert dI_ora[j] >= kth - tol, (j, dI_ora[j], kth)
+        else:
+            assert dI_ora[j] <= kth + tol, (j, dI_ora[j], kth)
+
+
+def compare_steps(wl, steps, tol, exact, seq_ids=None, k_override=None):
+    pk, runner = _pk()
+    cfg, W, pool, states, lens, tables, n_pages = oracle_batch(wl, seq_ids)
+    sess = runner.open_session(wl, DEV, seq_ids)
+    n, B = len(states), wl.block_size
+    outs = Outs(pk, wl, n)
+    ko_dev = None if k_override is None else torch.tensor(k_override, dtype=torch.int32, device=DEV)
+    stats = []
+    for step in range(steps):
+        print("step", step, flush=True)
+        masked_before = [list(st.masked) for st in states]
+        sess.focus.focus_step(n, k_override=ko_dev, out=outs.struct)
+        g = outs.host()
+        keep_gpu = [positions_of(u64(g["keep_bits"][b]), B) for b in range(n)]
+        if exact:
+            tr = fo.focus_step(cfg, W, pool, states, k_override=k_override,
+                               score_cast=lambda d: d.astype(np.float32).astype(np.float64),
+                               conf_cast=lambda c: c.astype(np.float32).astype(np.float64))
+        else:
+            tr = fo.focus_step(cfg, W, pool, states, keep_override=keep_gpu)
+        # scores
+        e_dI = max(relerr(g["delta_I"][b], tr.delta_I[b]) for b in range(n))
+        e_I = max(relerr(g["importance"][b], tr.I_evict[b]) for b in range(n))
+        assert e_I <= tol and e_dI <= max(tol, 5 * tol if not exact else tol), (e_I, e_dI)
+        for b in range(n):
+            assert abs(float(g["importance"][b].sum()) - B * wl.n_q_heads) < 1e-2 * B * wl.n_q_heads * tol + 1e-3
+        # decisions
+        if exact:
+            assert [int(k) for k in g["K"]] == tr.K
+            assert keep_gpu == tr.keep
+        else:
+            for b in range(n):
+                Kb = int(g["K"][b])
+                scale = float(np.max(np.abs(tr.delta_I[b])))
+                check_selection_valid(tr.delta_I[b], masked_before[b], set(keep_gpu[b]), Kb, B, 5 * tol * scale)
+        assert [int(x) for x in g["cu_seqlens"]] == tr.cu
+        T = tr.cu[-1]
+        assert [int(x) for x in g["row_map"][:T]] == tr.row_map
+        # floats
+        e_hf = relerr(g["hidden_full"], tr.hidden_full)
+        e_hp = relerr(g["hidden_packed"][:T], tr.hidden_packed)
+        e_lg = row_relerr(g["logits"][:T], tr.logits)
+        e_cf = relerr(g["conf"][:T], np.asarray(tr.conf)) if T else 0.0
+        stats.append(dict(step=step, T=T, dI=e_dI, hidden_full=e_hf, hidden_packed=e_hp, logits=e_lg, conf=e_cf))
+        print(stats[-1], flush=True)
+        assert e_hf <= tol and e_hp <= tol and e_lg <= tol, stats[-1]
+        # commit
+        gm = [u64(x) for x in g["mask_bits"]]
+        if exact:
+            assert np.array_equal(g["argmax"][:T], tr.argmax)
+            assert e_cf <= tol
+            for b, st in enumerate(states):
+                assert gm[b] == bits_of([p for p in range(B) if st.masked[p]])
+                assert [int(t) for t in g["tokens"][b]] == st.tokens
+                assert int(g["n_decoded"][b]) == tr.n_decoded[b]
+        else:
+            # accept the GPU's commit if it is valid for the oracle's logits within tolerance, then adopt it
+            for b, st in enumerate(states):
+                sl = slice(tr.cu[b], tr.cu[b + 1])
+                newly = [p for p in range(B) if masked_before[b][p] and not (gm[b] >> p) & 1]
+                assert len(newly) == int(g["n_decoded"][b])
+                cand = [(i, p) for i, p in enumerate(tr.keep[b]) if masked_before[b][p]]
+                if cand:
+                    assert len(newly) >= 1
+                    best = max(float(tr.conf[sl][i]) for i, _ in cand)
+                    thr = float(np.float32(wl.conf_threshold))
+                    for p in newly:
+                        i = tr.keep[b].index(p)
+                        c = float(tr.conf[sl][i])
+                        assert c >= thr * (1 - 5 * tol) or c >= best * (1 - 5 * tol), (b, p, c, best)
+                        lg = tr.logits[sl][i]
+                        tok = int(g["tokens"][b][p])
+                        assert lg[tok] >= lg.max() - 5 * tol * np.max(np.abs(lg)), (b, p)
+                        st.tokens[p] = tok
+                    # undo the oracle's own commit where it differs, adopt the GPU's
+                    for p in range(B):
+                        st.masked[p] = bool((gm[b] >> p) & 1)
+                        if st.masked[p]:
+                            st.tokens[p] = cfg.mask_token_id
+                    st.token_sum += len(newly) - tr.n_decoded[b]
+        for b in range(n):
+            s = sess.focus.focus_get_state(b)
+            assert (s.token_sum, s.total_steps, s.prefix_len) == (states[b].token_sum, states[b].total_steps, lens[sess.seq_ids[b]])
+            assert s.processed_bits == bits_of([p for p in range(B) if states[b].processed[p]])
+    sess.focus.focus_free()
+    return stats
+
+
+# ---------------------------------------------------------------------------------------------
+
+def test_c1_tiny_fp32_four_steps_exact():
+    """BASELINE configs[0]: real prefill, four denoising steps, fp32 on both sides, zero divergences."""
+    wl = fi.workload("c1_tiny")
+    pk, runner = _pk()
+    # prefix K/V written by the GPU prefill equals the oracle's
+    cfg, W, pool, states, lens, tables, n_pages = oracle_batch(wl)
+    sess = runner.open_session(wl, DEV)
+    kv = sess.kv_pool.cpu().numpy()
+    for l in range(wl.n_layers):
+        for b, st in enumerate(states):
+            for t in range(st.prefix_len):
+                pg = pool.layers[l][st.pages[t // wl.page_size]]
+                got = kv[l, st.pages[t // wl.page_size], :, :, t % wl.page_size, :]
+                assert relerr(got, pg[:, :, t % wl.page_size, :]) <= 1e-3, (l, b, t)
+    sess.focus.focus_free()
+    stats = compare_steps(wl, wl.steps, 1e-3, exact=True)
+    assert len(stats) == 4 and all(s["T"] == 16 for s in stats)
+
+
+@pytest.mark.parametrize("variant", ["dynamic", "constraints", "evict2", "override", "dense", "rawI"])
+def test_c1_variants_fp32_exact(variant):
+    over = dict(dynamic=dict(budget_mode=2, alpha=1.5, steps=3),
+                constraints=dict(constraints=3, steps=3),
+                evict2=dict(n_layers=4, evict_layer=2, steps=2),
+                override=dict(budget_mode=3, steps=2),
+                dense=dict(keep_ratio=1.0, steps=2),
+                rawI=dict(importance_mode=1, maxpool_k=1, steps=2))[variant]
+    wl = fi.workload("c1_tiny", **over)
+    ko = wl.k_overrides() if variant == "override" else None
+    compare_steps(wl, wl.steps, 1e-3, exact=True, k_override=ko)
+
+
+def small_bf16(**over):
+    base = dict(n_layers=3, hidden=512, n_q_heads=8, n_kv_heads=2, ffn=1024, vocab=4096, mask_token_id=4095,
+                batch=5, prefix_lo=70, prefix_hi=200, prefix_dist="uniform", block_size=32, budget_mode=1,
+                keep_ratio=0.25, steps=3, shuffle_pages=True)
+    base.update(over)
+    return fi.workload("c3_llada36", **base)
+
+
+def test_small_bf16_teacher_forced():
+    compare_steps(small_bf16(), 3, 2e-2, exact=False)
+
+
+def test_small_bf16_block64_override_empty_and_full():
+    wl = small_bf16(block_size=64, budget_mode=3, batch=4, steps=2)
+    compare_steps(wl, 2, 2e-2, exact=False, k_override=[0, 64, 17, 1])
+
+
+# ---------------------------------------------------------------------------------------------
+# stage tests: identical scores in, identical integers out
+
+def install_states(pk, sess, wl, masks, sums, steps):
+    for b, (m, ts, st) in enumerate(zip(masks, sums, steps)):
+        s = sess.focus.focus_get_state(b)
+        s.mask_bits, s.token_sum, s.total_steps = m, ts, st
+        sess.focus.focus_set_state(b, s)
+
+
+@pytest.mark.parametrize("mode,constraints", [(0, 0), (1, 0), (2, 0), (2, 3), (3, 1), (1, 2)])
+def test_select_compact_stage_bit_exact(mode, constraints):
+    pk, runner = _pk()
+    B, n = 32, 37
+    wl = fi.workload("c1_tiny", block_size=B, batch=n, budget_mode=mode, topk=3, keep_ratio=0.2, constraints=constraints,
+                     prefill="synthetic", n_layers=2)
+    sess = runner.open_session(wl, DEV)
+    cfg = oracle_config(wl)
+    r = np.random.default_rng(100 + mode * 10 + constraints)
+    for trial in range(4):
+        dI = r.normal(size=(n, B)).astype(np.float32)
+        dI = np.round(dI * 4) / 4 if trial % 2 else dI                     # coarse values: many exact ties
+        if trial == 3:
+            dI[0, :] = 0.0
+            dI[1, 5] = np.nan
+        masks = [int(r.integers(0, 1 << B)) for _ in range(n)]
+        masks[2] = 0
+        masks[3] = (1 << B) - 1
+        sums = [int(r.integers(0, 40)) for _ in range(n)]
+        stp = [int(r.integers(0, 9)) for _ in range(n)]
+        ko = [int(r.integers(0, B + 1)) for _ in range(n)]
+        install_states(pk, sess, wl, masks, sums, stp)
+        outs = Outs(pk, wl, n)
+        sess.focus.focus_select_compact(n, torch.from_numpy(dI).to(DEV), outs.struct,
+                                        k_override=torch.tensor(ko, dtype=torch.int32, device=DEV) if mode == 3 else None)
+        g = outs.host()
+        keep = []
+        for b in range(n):
+            masked = [bool((masks[b] >> p) & 1) for p in range(B)]
+            K = fo.budget(cfg, dI[b].astype(np.float64), masked, sums[b], stp[b], ko[b])
+            assert int(g["K"][b]) == K, (trial, b)
+            S = fo.select(cfg, dI[b].astype(np.float64), masked, [False] * B, K)
+            assert positions_of(u64(g["keep_bits"][b]), B) == S, (trial, b)
+            keep.append(S)
+        cu, rm = fo.compact(keep, B)
+        assert [int(x) for x in g["cu_seqlens"]] == cu
+        assert [int(x) for x in g["row_map"][:cu[-1]]] == rm
+    sess.focus.focus_free()
+
+
+def test_commit_stage_bit_exact():
+    pk, runner = _pk()
+    B, n = 32, 41
+    wl = fi.workload("c1_tiny", block_size=B, batch=n, conf_threshold=0.6, prefill="synthetic")
+    sess = runner.open_session(wl, DEV)
+    cfg = oracle_config(wl)
+    r = np.random.default_rng(7)
+    for trial in range(3):
+        masks = [int(r.integers(0, 1 << B)) for _ in range(n)]
+        keeps = [sorted(r.choice(B, size=int(r.integers(0, B + 1)), replace=False).tolist()) for _ in range(n)]
+        keeps[0], masks[1] = [], 0
+        install_states(pk, sess, wl, masks, [3] * n, [2] * n)
+        cu, _ = fo.compact(keeps, B)
+        conf = r.random(cu[-1]).astype(np.float32)
+        conf = np.round(conf * 8) / 8 if trial == 1 else conf            # ties in the forced-commit path
+        if trial == 2:
+            conf = conf * 0.5                                             # nothing passes: forced commits only
+        am = r.integers(1, wl.vocab, cu[-1]).astype(np.int32)
+        outs = Outs(pk, wl, n)
+        sess.focus.focus_commit(n, torch.tensor([bits_of(k) for k in keeps], dtype=torch.int64, device=DEV),
+                                torch.tensor(cu, dtype=torch.int32, device=DEV), torch.from_numpy(conf).to(DEV),
+                                torch.from_numpy(am).to(DEV), outs.struct)
+        g = outs.host()
+        for b in range(n):
+            st = fo.new_seq_state(cfg, 0, [])
+            st.masked = [bool((masks[b] >> p) & 1) for p in range(B)]
+            st.token_sum, st.total_steps = 3, 2
+            D = fo.commit(cfg, st, keeps[b], conf[cu[b]:cu[b + 1]], am[cu[b]:cu[b + 1]])
+            assert u64(g["mask_bits"][b]) == bits_of([p for p in range(B) if st.masked[p]]), (trial, b)
+            assert int(g["n_decoded"][b]) == len(D)
+            got = [int(t) for t in g["tokens"][b]]
+            assert [got[p] for p in D] == [st.tokens[p] for p in D]
+            s = sess.focus.focus_get_state(b)
+            assert (s.token_sum, s.total_steps) == (st.token_sum, st.total_steps)
+    sess.focus.focus_free()
+
+
+def test_run_twice_bitwise_and_slot_permutation():
+    pk, runner = _pk()
+    wl = small_bf16(batch=4, steps=1)
+    res = []
+    for perm in (None, None, [2, 0, 3, 1]):
+        sess = runner.open_session(wl, DEV)
+        n = wl.batch
+        outs = Outs(pk, wl, n)
+        slot = None if perm is None else torch.tensor(perm, dtype=torch.int32, device=DEV)
+        sess.focus.focus_step(n, seq_slot=slot, out=outs.struct)
+        res.append(outs.host())
+        sess.focus.focus_free()
+    a, b, c = res
+    for k in a:
+        assert np.array_equal(a[k], b[k]), k                              # same call, same bits
+    B = wl.block_size
+    for newb, oldb in enumerate([2, 0, 3, 1]):                            # batch order permuted: rows move with it
+        assert c["keep_bits"][newb] == a["keep_bits"][oldb]
+        ra = slice(a["cu_seqlens"][oldb], a["cu_seqlens"][oldb + 1])
+        rc = slice(c["cu_seqlens"][newb], c["cu_seqlens"][newb + 1])
+        assert np.array_equal(c["logits"][rc], a["logits"][ra])
+        assert np.array_equal(c["tokens"][newb], a["tokens"][oldb])
+
+
+def test_step_argument_errors():
+    pk, runner = _pk()
+    wl = fi.workload("c1_tiny", budget_mode=3)
+    sess = runner.open_session(wl, DEV)
+    with pytest.raises(pk.FocusError):
+        sess.focus.focus_step(wl.batch)                    # OVERRIDE without budgets
+    with pytest.raises(pk.FocusError):
+        sess.focus.focus_step(wl.batch + 1)                # more sequences than slots
+    with pytest.raises(pk.FocusError):
+        sess.focus.focus_prefill_kv([10_000], [[0]])       # prefix longer than planned
+    with pytest.raises(pk.FocusError):
+        sess.focus.focus_prefill_kv([8], [[999]])          # page outside the pool
+    sess.focus.focus_free()
