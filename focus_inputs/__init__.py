@@ -76,10 +76,13 @@ def normal_values(seed: int, tensor_id: int, start: int, count: int, std: float,
 
 
 def fill_normal_(out: torch.Tensor, seed: int, tensor_id: int, std: float,
-                 chunk: int = 1 << 26) -> torch.Tensor:
-    """Fill a contiguous tensor in place, flat index = row-major element offset."""
+                 chunk: Optional[int] = None) -> torch.Tensor:
+    """Fill a contiguous tensor in place, flat index = row-major element offset.  The chunk size only
+    shapes the temporaries (cache-sized on the CPU, large on the GPU); values do not depend on it."""
     flat = out.view(-1)
     n = flat.numel()
+    if chunk is None:
+        chunk = (1 << 18) if out.device.type == "cpu" else (1 << 26)
     for s in range(0, n, chunk):
         c = min(chunk, n - s)
         flat[s:s + c] = normal_values(seed, tensor_id, s, c, std, device=out.device, dtype=out.dtype)

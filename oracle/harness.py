@@ -30,7 +30,22 @@ def _f64(t) -> np.ndarray:
     return t.to(dtype=__import__("torch").float64).numpy()
 
 
-def oracle_weights(wl: Workload, cache_layers: bool = True) -> fo.Weights:
+class LazyRows:
+    """Embedding table whose rows are generated when they are indexed (a 150k x 4096 table is 5 GB in
+    float64 and a step only looks up a handful of ids)."""
+
+    def __init__(self, wl: Workload):
+        self.wl = wl
+
+    def __getitem__(self, ids) -> np.ndarray:
+        from focus_inputs import TID_EMBED, WEIGHT_STD, normal_values
+        h = self.wl.hidden
+        rows = [_f64(normal_values(self.wl.seed, TID_EMBED, int(i) * h, h, WEIGHT_STD, dtype=self.wl.torch_dtype))
+                for i in np.asarray(ids).reshape(-1)]
+        return np.stack(rows) if rows else np.zeros((0, h))
+
+
+def oracle_weights(wl: Workload, cache_layers: bool = True, lazy_embed: bool = False) -> fo.Weights:
     """Float64 copies of the workload's weights (bf16 workloads: the bf16 bit patterns widened).
     Layers are generated on first use; with cache_layers=False each fetch regenerates (large models)."""
     cache: Dict[int, Dict[str, np.ndarray]] = {}
@@ -46,15 +61,15 @@ def oracle_weights(wl: Workload, cache_layers: bool = True) -> fo.Weights:
             cache[l] = w
         return w
 
-    return fo.Weights(_f64(wl.embed()), _f64(wl.lm_head()), ones, layer)
+    return fo.Weights(LazyRows(wl) if lazy_embed else _f64(wl.embed()), _f64(wl.lm_head()), ones, layer)
 
 
-def oracle_batch(wl: Workload, seq_ids: Optional[Sequence[int]] = None):
+def oracle_batch(wl: Workload, seq_ids: Optional[Sequence[int]] = None, lazy_embed: bool = False):
     """Oracle pool + per-sequence states for the listed sequences of the workload's batch (default all),
     with the prefix K/V in place: seeded synthetic pages, or a real prefill of the seeded prompts.
     Returns (cfg, weights, pool, states, prefix_lens, page_tables, n_pages_total)."""
     cfg = oracle_config(wl)
-    W = oracle_weights(wl, cache_layers=wl.n_layers <= 8)
+    W = oracle_weights(wl, cache_layers=wl.n_layers <= 8, lazy_embed=lazy_embed)
     lens = wl.prefix_lens()
     tables, n_pages = wl.page_tables(lens)
     ids = list(range(wl.batch)) if seq_ids is None else list(seq_ids)

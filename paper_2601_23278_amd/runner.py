@@ -34,6 +34,20 @@ class Session:
     n_pages: int
     kv_pool: torch.Tensor
     seq_ids: List[int]
+    weights: tuple = ()
+
+    def reopen(self, **cfg_over) -> "Session":
+        """Frees the context and creates a new one over the same weights, K/V pool and workspace with some
+        configuration members replaced (e.g. keep_ratio), then re-installs the sequences (new block)."""
+        cfg = self.focus.cfg
+        for k, v in cfg_over.items():
+            setattr(cfg, k, v)
+        ws = self.focus.workspace
+        self.focus.focus_free()
+        embed, lm_head, norm, layers = self.weights
+        self.focus = Focus(cfg, embed, lm_head, norm, layers, self.kv_pool, ws)
+        self.focus.focus_prefill_kv(self.prefix_lens, self.page_tables, None)
+        return self
 
 
 def open_session(wl: Workload, device="cuda:0", seq_ids: Optional[Sequence[int]] = None, **cfg_over) -> Session:
@@ -66,4 +80,4 @@ def open_session(wl: Workload, device="cuda:0", seq_ids: Optional[Sequence[int]]
         all_prompts = wl.prompt_tokens(lens_all)
         prompts = [all_prompts[b] for b in ids]
     f.focus_prefill_kv(lens, tables, prompts)
-    return Session(wl, f, lens, tables, n_pages, pool, ids)
+    return Session(wl, f, lens, tables, n_pages, pool, ids, (embed, lm_head, norm, layers))
