@@ -69,11 +69,146 @@ static void launch_valu(hipStream_t s, const void *A, const void *W, int N, int 
     k_gemm_valu<T, EPI_STORE_F32><<<grid, 256, 0, s>>>((const T *)A, (const T *)W, N, K, rows, out, ldo);
 }
 
+// ---------------------------------------------------------------------------------------------
+// bf16 on the matrix cores.
+//
+// Workgroup = 4 wavefronts (2 x 2), macro tile BM x BN x 64; each wavefront owns a (BM/2) x (BN/2) patch as
+// 32x32 accumulator tiles of v_mfma_f32_32x32x16_bf16.  Both operands are K-contiguous, so A rows and W rows
+// feed the instruction the same way: lane l supplies row l % 32, eight consecutive k starting at 8 * (l / 32).
+//
+// LDS holds one K-slab of each operand, rows of 64 bf16 = 128 B = eight 16-byte chunks; chunk c of row r is
+// stored at chunk position c ^ (r & 7), so the 32 rows read by one ds_read_b128 spread over all banks and
+// the 8 lanes that fill a row write distinct chunks.  The next K-slab is fetched from global memory into
+// registers while the current one is multiplied (two workgroups per CU overlap each other's barriers).
+//
+// Workgroup ids are dealt round-robin to the 8 XCDs by the hardware; the id is remapped so that each XCD
+// works on one contiguous range of tiles (ordered in groups of 8 tile rows), which keeps the A and W panels a
+// range touches inside that XCD's own L2.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+template <int BM, int BN, int EPI>
+__global__ __launch_bounds__(256, 2) void k_gemm_mfma(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W, int N, int K,
+                                                      Rows rows, void *out, int ldo, int tiles_m, int tiles_n) {
+  constexpr int BK = 64, WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
+  constexpr int CA = BM * 8 / 256, CB = BN * 8 / 256;      // 16-byte chunks per thread and K-slab
+  __shared__ __attribute__((aligned(16))) unsigned char As[BM * 128];
+  __shared__ __attribute__((aligned(16))) unsigned char Bs[BN * 128];
+
+  const int M = rows.count ? min(*rows.count, rows.cap) : rows.cap;
+  // XCD-aware tile order
+  const int total = tiles_m * tiles_n;
+  const int per_xcd = (total + 7) / 8;
+  const int tile = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  if (blockIdx.x / 8 >= per_xcd || tile >= total) return;
+  constexpr int GROUP = 8;
+  const int in_group = tile % (GROUP * tiles_n), first_m = (tile / (GROUP * tiles_n)) * GROUP;
+  const int gsz = min(tiles_m - first_m, GROUP);
+  const int m0 = (first_m + in_group % gsz) * BM, n0 = (in_group / gsz) * BN;
+  if (m0 >= M) return;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = (wave >> 1) * WM, wn = (wave & 1) * WN;
+
+  // global -> register -> LDS staging: chunk id = tid + 256 * i -> (row, chunk)
+  const bf16_t *ga[CA], *gb[CB];
+  int sa[CA], sb[CB];
+#pragma unroll
+  for (int i = 0; i < CA; ++i) {
+    int c = tid + 256 * i, r = c >> 3, ch = c & 7;
+    ga[i] = A + (size_t)min(m0 + r, M - 1) * K + ch * 8;
+    sa[i] = r * 128 + ((ch ^ (r & 7)) << 4);
+  }
+#pragma unroll
+  for (int i = 0; i < CB; ++i) {
+    int c = tid + 256 * i, r = c >> 3, ch = c & 7;
+    gb[i] = W + (size_t)min(n0 + r, N - 1) * K + ch * 8;
+    sb[i] = r * 128 + ((ch ^ (r & 7)) << 4);
+  }
+  u32x4 ra[CA], rb[CB];
+#pragma unroll
+  for (int i = 0; i < CA; ++i) ra[i] = *(const u32x4 *)(ga[i]);
+#pragma unroll
+  for (int i = 0; i < CB; ++i) rb[i] = *(const u32x4 *)(gb[i]);
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // fragment addresses: row = base + (lane & 31), logical chunk = 2 * ks + (lane >> 5)
+  const int frow = lane & 31, fch = lane >> 5;
+  const int nk = K / BK;
+  for (int kt = 0; kt < nk; ++kt) {
+#pragma unroll
+    for (int i = 0; i < CA; ++i) *(u32x4 *)(As + sa[i]) = ra[i];
+#pragma unroll
+    for (int i = 0; i < CB; ++i) *(u32x4 *)(Bs + sb[i]) = rb[i];
+    __syncthreads();
+    {
+      // the last iteration re-reads its own slab: an unconditional load keeps the staging registers in VGPRs
+      const size_t koff = (size_t)min(kt + 1, nk - 1) * BK;
+#pragma unroll
+      for (int i = 0; i < CA; ++i) ra[i] = *(const u32x4 *)(ga[i] + koff);
+#pragma unroll
+      for (int i = 0; i < CB; ++i) rb[i] = *(const u32x4 *)(gb[i] + koff);
+    }
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      bf16x8 af[TM], bfr[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        int r = wm + i * 32 + frow;
+        af[i] = *(const bf16x8 *)(As + r * 128 + (((2 * ks + fch) ^ (r & 7)) << 4));
+      }
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        int r = wn + j * 32 + frow;
+        bfr[j] = *(const bf16x8 *)(Bs + r * 128 + (((2 * ks + fch) ^ (r & 7)) << 4));
+      }
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    }
+    __syncthreads();
+  }
+
+  // epilogue: accumulator register r of lane l is C[8 * (r / 4) + 4 * (l / 32) + r % 4][l % 32] of its 32x32 tile
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int gn = n0 + wn + j * 32 + (lane & 31);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int gm = m0 + wm + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        if (gm < M && gn < N) store_out<bf16_t, EPI>(out, (size_t)gm * ldo + gn, acc[i][j][r]);
+      }
+    }
+}
+
+template <int BM, int BN>
+static void launch_mfma(hipStream_t s, const void *A, const void *W, int N, int K, Rows rows, int epi, void *out, int ldo) {
+  const int tiles_m = (rows.cap + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+  const int grid = ((tiles_m * tiles_n + 7) / 8) * 8;
+  const bf16_t *a = (const bf16_t *)A, *w = (const bf16_t *)W;
+  if (epi == EPI_STORE) k_gemm_mfma<BM, BN, EPI_STORE><<<grid, 256, 0, s>>>(a, w, N, K, rows, out, ldo, tiles_m, tiles_n);
+  else if (epi == EPI_ADD_F32) k_gemm_mfma<BM, BN, EPI_ADD_F32><<<grid, 256, 0, s>>>(a, w, N, K, rows, out, ldo, tiles_m, tiles_n);
+  else k_gemm_mfma<BM, BN, EPI_STORE_F32><<<grid, 256, 0, s>>>(a, w, N, K, rows, out, ldo, tiles_m, tiles_n);
+}
+
 void gemm(hipStream_t s, int dtype, const void *A, const void *W, int N, int K, Rows rows, int epilogue,
           void *out, int ldo) {
   if (rows.cap <= 0) return;
-  if (dtype == FOCUS_F32) launch_valu<float>(s, A, W, N, K, rows, epilogue, out, ldo);
-  else launch_valu<bf16_t>(s, A, W, N, K, rows, epilogue, out, ldo);
+  if (dtype == FOCUS_F32) { launch_valu<float>(s, A, W, N, K, rows, epilogue, out, ldo); return; }
+  const bool aligned = K % 64 == 0 && ((uintptr_t)A & 15) == 0 && ((uintptr_t)W & 15) == 0;
+  if (!aligned) { launch_valu<bf16_t>(s, A, W, N, K, rows, epilogue, out, ldo); return; }
+  launch_mfma<256, 128>(s, A, W, N, K, rows, epilogue, out, ldo);
 }
 
 }  // namespace fk
