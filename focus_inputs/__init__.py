@@ -225,15 +225,18 @@ class Workload:
         return 2 * self.n_kv_heads * self.page_size * self.head_dim
 
     def kv_pool_fill_(self, pool: torch.Tensor) -> torch.Tensor:
-        """Fill a whole pool laid out [layer, page, 2, H_kv, page_size, D] with seeded K/V."""
+        """Fill a whole pool [layer, page, page_elems] with seeded K/V.  A page holds K as [H_kv, page_size, D]
+        followed by V transposed, [H_kv, D, page_size] (the library's cache layout)."""
         return fill_normal_(pool, self.seed, TID_KV, KV_STD)
 
     def kv_page(self, layer: int, page: int, n_pages: int, device="cpu") -> torch.Tensor:
-        """One page of the seeded pool, [2, H_kv, page_size, D], same bits as kv_pool_fill_."""
+        """One page of the seeded pool as (K, V), both [H_kv, page_size, D], same bits as kv_pool_fill_."""
         e = self.kv_page_elems()
         v = normal_values(self.seed, TID_KV, (layer * n_pages + page) * e, e, KV_STD, device=device,
                           dtype=self.torch_dtype)
-        return v.view(2, self.n_kv_heads, self.page_size, self.head_dim)
+        k = v[:e // 2].view(self.n_kv_heads, self.page_size, self.head_dim)
+        vt = v[e // 2:].view(self.n_kv_heads, self.head_dim, self.page_size)
+        return torch.stack([k, vt.transpose(1, 2)])
 
 
 _SHAPE_8B = dict(hidden=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, ffn=12288, vocab=151936,

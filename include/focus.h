@@ -24,9 +24,11 @@
  *   - Matrices are row-major [out_features, in_features]; element type per focus_config.dtype.
  *   - w_qkv rows: H_q*D query rows, then H_kv*D key rows, then H_kv*D value rows.
  *     w_gate_up rows: F gate rows, then F up rows.
- *   - K/V pool: [n_layers][n_pages][2 (K,V)][H_kv][page_size][D], element type per dtype.  K is stored
- *     after the rotary embedding.  A sequence's token t lives in page page_table[t / page_size] at row
- *     t % page_size; the current block occupies tokens prefix_len .. prefix_len + B - 1.
+ *   - K/V pool: [n_layers][n_pages] pages, element type per dtype.  A page holds K as [H_kv][page_size][D]
+ *     (after the rotary embedding) followed by V transposed, [H_kv][D][page_size], so that both operands of
+ *     the attention contractions are contiguous along the contracted index.  A sequence's token t lives in
+ *     page page_table[t / page_size] at row (K) / column (V) t % page_size; the current block occupies tokens
+ *     prefix_len .. prefix_len + B - 1.
  *   - Bit sets over block positions are uint64_t, bit p = position p (B <= 64).
  *   - Packed rows: sequences in batch order, positions ascending; row_map[r] = b * B + p.
  */

@@ -14,14 +14,15 @@ namespace {
 std::string g_error;   // last error of a call that had no context
 
 constexpr int kMaxTimed = 4096;
+constexpr int kTargetAttnGroups = 2048;   // (sequence, kv head, split) workgroups the attention launch aims for
 
 struct Plan {
   size_t off_prefix_len, off_page_table, off_tokens, off_mask, off_processed, off_token_sum, off_total_steps;
   size_t off_rope, off_resid, off_resid_p, off_normed, off_qkv, off_q_p, off_attn, off_gate_up, off_act, off_logits;
   size_t off_partial, off_delta, off_K, off_keep, off_n_keep, off_vis, off_cu, off_cu_full, off_row_map,
       off_row_map_full, off_total, off_total_full, off_conf, off_argmax, off_prompt, off_prompt_off, off_prompt_len,
-      off_slot_list;
-  size_t bytes;
+      off_slot_list, off_part_o, off_part_ml;
+  size_t bytes, part_entries;
   int table_stride, max_rows, max_pos;
 };
 
@@ -71,6 +72,11 @@ Plan make_plan(const focus_config &c) {
   p.off_prompt_off = take(nb * 4);
   p.off_prompt_len = take(nb * 4);
   p.off_slot_list = take(nb * 4);
+  // split-K/V partials of the attention: (row, head, split) entries; the launch policy keeps
+  // rows * H_q * splits within  B * group * kTargetAttnGroups + max_rows * H_q
+  p.part_entries = c.dtype == FOCUS_BF16 ? (size_t)B * (c.n_q_heads / c.n_kv_heads) * kTargetAttnGroups + rows * c.n_q_heads : 0;
+  p.off_part_o = take(p.part_entries * c.head_dim * 4);
+  p.off_part_ml = take(p.part_entries * 2 * 4);
   p.bytes = at;
   return p;
 }
@@ -111,6 +117,7 @@ struct focus_ctx {
   std::vector<int> ev_class;
   int n_timed = 0;
   hipStream_t last_stream = nullptr;
+  int max_total = 0;                   // host-side bound of prefix_len + B over the installed sequences
 
   template <typename T> T *at(size_t off) const { return (T *)(ws + off); }
   fk::SlotState slots() const {
@@ -162,7 +169,15 @@ struct Timed {
 struct RowSet {        // a set of rows the layers run on
   fk::Rows rows;
   fk::RowIndex ri;
+  int n_seq;
+  const int32_t *cu;   // rows of sequence b: cu[b] .. cu[b + 1]
+  int max_rows_per_seq;
 };
+
+// K/V split size for the attention launch: whole sequences when there are enough (sequence, kv head) groups
+// to fill the chip, otherwise cut so that about kTargetAttnGroups workgroups exist; always a multiple of the
+// 64-token tile and never so small that the partial buffer would overflow.
+void attention_split(const focus_ctx *c, int n_seq, int rows_cap, int *chunk, int *splits);
 
 // rmsnorm -> QKV projection -> rotary + K/V write, for every row of the set (App. C ordering).
 void layer_qkv(focus_ctx *c, hipStream_t s, int l, const RowSet &rs, const float *resid) {
@@ -183,12 +198,33 @@ void layer_rest(focus_ctx *c, hipStream_t s, int l, const RowSet &rs, float *res
   void *normed = c->at<char>(c->plan.off_normed), *attn = c->at<char>(c->plan.off_attn);
   void *gate_up = c->at<char>(c->plan.off_gate_up), *act = c->at<char>(c->plan.off_act);
   { Timed t(c, s, FOCUS_KC_ATTENTION);
-    fk::attention(s, g.dtype, q, q_stride, g.n_q_heads, rs.rows, rs.ri, c->slots(), vis_by_b, c->kv_layer(l), attn); }
+    fk::AttnArgs a{};
+    a.dtype = g.dtype; a.q = q; a.q_stride = q_stride; a.n_q_heads = g.n_q_heads; a.n_seq = rs.n_seq; a.cu = rs.cu;
+    a.max_rows_per_seq = rs.max_rows_per_seq; a.rows = rs.rows; a.ri = rs.ri; a.st = c->slots(); a.vis_by_b = vis_by_b;
+    a.kv = c->kv_layer(l); a.out = attn;
+    a.part_o = c->plan.part_entries ? c->at<float>(c->plan.off_part_o) : nullptr;
+    a.part_ml = c->plan.part_entries ? c->at<float>(c->plan.off_part_ml) : nullptr;
+    attention_split(c, rs.n_seq, rs.rows.cap, &a.chunk, &a.launch_splits);
+    a.max_splits = a.launch_splits;
+    fk::attention(s, a); }
   { Timed t(c, s, FOCUS_KC_GEMM); fk::gemm(s, g.dtype, attn, c->w_o[l], g.hidden, q_w, rs.rows, fk::EPI_ADD_F32, resid, g.hidden); }
   { Timed t(c, s, FOCUS_KC_POINTWISE); fk::rmsnorm(s, g.dtype, resid, c->mlp_norm[l], normed, g.hidden, g.rms_eps, rs.rows); }
   { Timed t(c, s, FOCUS_KC_GEMM); fk::gemm(s, g.dtype, normed, c->w_gate_up[l], 2 * g.ffn, g.hidden, rs.rows, fk::EPI_STORE, gate_up, 2 * g.ffn); }
   { Timed t(c, s, FOCUS_KC_POINTWISE); fk::silu_mul(s, g.dtype, gate_up, act, g.ffn, rs.rows); }
   { Timed t(c, s, FOCUS_KC_GEMM); fk::gemm(s, g.dtype, act, c->w_down[l], g.hidden, g.ffn, rs.rows, fk::EPI_ADD_F32, resid, g.hidden); }
+}
+
+void attention_split(const focus_ctx *c, int n_seq, int rows_cap, int *chunk, int *splits) {
+  const focus_config &g = c->cfg;
+  const int max_total = c->max_total > 0 ? c->max_total : g.max_prefix_len + g.block_size;
+  const long groups = (long)n_seq * g.n_kv_heads;
+  long want = (groups >= kTargetAttnGroups) ? 1 : (kTargetAttnGroups + groups - 1) / groups;   // splits per sequence
+  long ch = ((max_total + want - 1) / want + 63) / 64 * 64;
+  if (ch < 256) ch = 256;
+  // partial buffer: rows * H_q * splits entries
+  while (c->plan.part_entries && (long)rows_cap * g.n_q_heads * ((max_total + ch - 1) / ch) > (long)c->plan.part_entries) ch *= 2;
+  *chunk = (int)ch;
+  *splits = (int)((max_total + ch - 1) / ch);
 }
 
 int check_batch(focus_ctx *ctx, int n_seq) {
@@ -344,6 +380,7 @@ int focus_set_state(focus_ctx *ctx, int32_t slot, const focus_seq_state *st) {
   for (int p = 0; p < B; ++p)
     if (st->tokens[p] < 0 || st->tokens[p] >= ctx->cfg.vocab) return fail(ctx, FOCUS_EINVAL, "token id %d at position %d outside the vocabulary", st->tokens[p], p);
   HIP_TRY(ctx, hipDeviceSynchronize());
+  if (st->prefix_len + B > ctx->max_total) ctx->max_total = st->prefix_len + B;
   HIP_TRY(ctx, hipMemcpy(s.prefix_len + slot, &st->prefix_len, 4, hipMemcpyHostToDevice));
   HIP_TRY(ctx, hipMemcpy(s.total_steps + slot, &st->total_steps, 4, hipMemcpyHostToDevice));
   HIP_TRY(ctx, hipMemcpy(s.token_sum + slot, &st->token_sum, 8, hipMemcpyHostToDevice));
@@ -390,6 +427,7 @@ int focus_prefill_kv(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int3
     for (long long i = 0; i < total_prompt; ++i)
       if (prompt_tokens[i] < 0 || prompt_tokens[i] >= g.vocab) return fail(ctx, FOCUS_EINVAL, "prompt token %lld outside the vocabulary", i);
   }
+  ctx->max_total = (max_len + B > ctx->max_total) ? max_len + B : ctx->max_total;
   fk::SlotState st = ctx->slots();
   // page tables: one row per slot
   for (int b = 0; b < n_seq; ++b)
@@ -407,7 +445,7 @@ int focus_prefill_kv(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int3
     uint64_t *keep = ctx->at<uint64_t>(pl.off_keep);
     int32_t *cu = ctx->at<int32_t>(pl.off_cu), *row_map = ctx->at<int32_t>(pl.off_row_map), *total = ctx->at<int32_t>(pl.off_total);
     float *resid = ctx->at<float>(pl.off_resid_p);
-    RowSet rs{{n_seq * B, total}, {row_map, d_slots, B}};
+    RowSet rs{{n_seq * B, total}, {row_map, d_slots, B}, n_seq, cu, B};
     const int qkv_w = (g.n_q_heads + 2 * g.n_kv_heads) * g.head_dim;
     for (int c0 = 0; c0 * B < max_len; ++c0) {
       fk::prefill_chunk_setup(s, n_seq, B, c0, d_slots, st, ctx->at<int32_t>(pl.off_prompt), d_off, d_len, keep);
@@ -455,7 +493,7 @@ int focus_step(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32_t *s
   float *logits = o.logits ? o.logits : ctx->at<float>(pl.off_logits);
 
   // phase 1: whole block through layers 0 .. e-1, layer e up to its K/V fill, importance of layers e-1 and e
-  RowSet full{{T0, nullptr}, {ctx->at<int32_t>(pl.off_row_map_full), seq_slot, B}};
+  RowSet full{{T0, nullptr}, {ctx->at<int32_t>(pl.off_row_map_full), seq_slot, B}, n_seq, ctx->at<int32_t>(pl.off_cu_full), B};
   { Timed t(ctx, s, FOCUS_KC_POINTWISE);
     fk::iota_rows(s, ctx->at<int32_t>(pl.off_row_map_full), ctx->at<int32_t>(pl.off_cu_full), n_seq, B, ctx->at<int32_t>(pl.off_total_full));
     fk::embed(s, g.dtype, ctx->embed, g.hidden, full.rows, full.ri, st, g.mask_token_id, resid); }
@@ -489,7 +527,7 @@ int focus_step(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32_t *s
     fk::scan_compact(s, n_seq, B, keep, cu, row_map, total);
   }
   const int cap = packed_cap(g, n_seq, keep_override != nullptr);
-  RowSet packed{{cap, total}, {row_map, seq_slot, B}};
+  RowSet packed{{cap, total}, {row_map, seq_slot, B}, n_seq, cu, n_seq > 0 ? (cap + n_seq - 1) / n_seq : 0};
   { Timed t(ctx, s, FOCUS_KC_EVICT);
     fk::gather_rows(s, g.dtype, packed.rows, row_map, resid, resid_p, g.hidden, qkv, qkv_w, q_p, q_w); }
 

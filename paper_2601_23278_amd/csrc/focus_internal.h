@@ -64,8 +64,23 @@ void gemm(hipStream_t s, int dtype, const void *A, const void *W, int N, int K, 
 // Rotates q and k rows of the fused qkv buffer in place and stores k, v of every row into its cache slot.
 void rope_kv_write(hipStream_t s, int dtype, void *qkv, int n_q_heads, Rows rows, RowIndex ri, SlotState st,
                    KvLayer kv, const float2 *rope_table);
-void attention(hipStream_t s, int dtype, const void *q, int q_stride, int n_q_heads, Rows rows, RowIndex ri,
-               SlotState st, const uint64_t *vis_by_b, KvLayer kv, void *out);
+struct AttnArgs {
+  int dtype;
+  const void *q;                 // [rows, q_stride] rotated queries, head h at column h * D
+  int q_stride, n_q_heads;
+  int n_seq;
+  const int32_t *cu;             // rows of sequence b are cu[b] .. cu[b + 1]
+  int max_rows_per_seq;          // host-known bound of cu[b + 1] - cu[b]
+  Rows rows;
+  RowIndex ri;
+  SlotState st;
+  const uint64_t *vis_by_b;      // visible in-block positions per batch entry, null = all
+  KvLayer kv;
+  void *out;                     // [rows, H_q * D]
+  float *part_o, *part_ml;       // split-K/V partials: [rows, H_q, max_splits, D] and [.., 2]
+  int chunk, max_splits, launch_splits;
+};
+void attention(hipStream_t s, const AttnArgs &a);
 // Eq. 2 per (sequence, query head) on the full-block qkv buffer: partial[b, h, j].
 void importance(hipStream_t s, int dtype, const void *qkv, int n_seq, int B, int n_q_heads, int n_kv_heads,
                 int head_dim, int maxpool_k, float *partial);

@@ -41,14 +41,14 @@ __global__ __launch_bounds__(64) void k_attn_rowwave(const T *__restrict__ q, in
   for (int t = 0; t < L + ri.B; ++t) {
     if (t >= L && !((vis >> (t - L)) & 1ull)) continue;
     const T *kp = (const T *)kv.base + (size_t)pt[t / P] * page_elems + ((size_t)hk * P + (t % P)) * D;
-    const T *vp = kp + (size_t)Hkv * P * D;
+    const T *vp = (const T *)kv.base + (size_t)pt[t / P] * page_elems + (size_t)(Hkv + hk) * P * D + (t % P);
     float s = 0.f;
     for (int e = 0; e < NE; ++e) s += qv[e] * to_f(kp[lane + 64 * e]);
     s = wave_sum(s);
     float mn = fmaxf(m, s);
     float corr = __expf(m - mn), pr = __expf(s - mn);
     l = l * corr + pr;
-    for (int e = 0; e < NE; ++e) o[e] = o[e] * corr + pr * to_f(vp[lane + 64 * e]);
+    for (int e = 0; e < NE; ++e) o[e] = o[e] * corr + pr * to_f(vp[(size_t)(lane + 64 * e) * P]);
     m = mn;
   }
   T *orow = out + (size_t)r * Hq * D + (size_t)hq * D;
@@ -56,17 +56,253 @@ __global__ __launch_bounds__(64) void k_attn_rowwave(const T *__restrict__ q, in
   for (int e = 0; e < NE; ++e) orow[lane + 64 * e] = (T)(o[e] * inv);
 }
 
-void attention(hipStream_t s, int dtype, const void *q, int q_stride, int n_q_heads, Rows rows, RowIndex ri,
-               SlotState st, const uint64_t *vis_by_b, KvLayer kv, void *out) {
-  if (rows.cap <= 0) return;
-  dim3 grid(rows.cap, n_q_heads);
-  const int ne = kv.head_dim / 64;
-  if (dtype == FOCUS_F32) {
-    if (ne == 1) k_attn_rowwave<float, 1><<<grid, 64, 0, s>>>((const float *)q, q_stride, n_q_heads, rows, ri, st, vis_by_b, kv, (float *)out);
-    else k_attn_rowwave<float, 2><<<grid, 64, 0, s>>>((const float *)q, q_stride, n_q_heads, rows, ri, st, vis_by_b, kv, (float *)out);
+// ---------------------------------------------------------------------------------------------
+// bf16 attention on the matrix cores, one workgroup per (sequence, kv head, K/V split).
+//
+// All query rows of the sequence that share the kv head (rows x group heads, up to 32 per wavefront) are
+// multiplied against each 64-token K/V tile, so the K/V stream is read from HBM once per (sequence, kv head)
+// whatever the number of rows: the kernel is bound by that stream.
+//
+// Per tile and wavefront:  S^T = K Q^T  (v_mfma_f32_32x32x16_bf16, A = K rows from LDS, B = Q held in
+// registers), so that a lane owns one query row and its scores sit in its own registers: the online-softmax
+// max/sum are in-lane reductions plus one exchange between lanes l and l + 32.  O^T = V^T P^T then takes
+// the probabilities straight from those registers as the B operand.  For that, lane l of the first product
+// loads K row sigma(l % 32) (bits 2 and 3 swapped) instead of l % 32, which makes the eight probabilities a
+// lane holds for one product belong to eight consecutive tokens; V is cached transposed ([D][tokens]), so
+// the matching A operand is one 16-byte LDS read.
+//
+// LDS: K tile [64 tokens][128] and V^T tile [128][64 tokens], 16-byte chunks XOR-swizzled against bank
+// conflicts; the next tile is fetched into registers while the current one is used.
+// A page (64 tokens) is one tile.  Long sequences are cut into splits of `chunk` tokens; a split writes
+// un-normalised partial outputs and (max, sum), merged in split order by k_attn_combine.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ int sigma32(int i) { return (i & ~12) | ((i & 4) << 1) | ((i & 8) >> 1); }
+__device__ __forceinline__ int kkey(int token) { return (token & 3) | (((token >> 3) & 1) << 2); }
+
+template <int NW>
+__global__ __launch_bounds__(NW * 64) void k_attn_mfma(AttnArgs a) {
+  constexpr int D = 128, P = 64, NT = NW * 64, CPT = 1024 / NT;
+  __shared__ __attribute__((aligned(16))) unsigned char Ks[64 * 256];
+  __shared__ __attribute__((aligned(16))) unsigned char Vs[128 * 128];
+  const int Hkv = a.kv.n_kv_heads, Hq = a.n_q_heads, g = Hq / Hkv;
+  const int b = blockIdx.x / Hkv, hk = blockIdx.x % Hkv, split = blockIdx.y;
+  const int r0 = a.cu[b], nr = a.cu[b + 1] - r0;
+  if (nr <= 0) return;
+  const int slot = slot_of(a.ri.seq_slot, b, a.st);
+  const int L = a.st.prefix_len[slot], total = L + a.ri.B;
+  const int t0 = split * a.chunk;
+  if (t0 >= total) return;
+  const int t1 = min(t0 + a.chunk, total);
+  const int nsplit = (total + a.chunk - 1) / a.chunk;
+  const uint64_t vis = a.vis_by_b ? a.vis_by_b[b] : ~0ull;
+  const int32_t *pt = a.st.page_table + (size_t)slot * a.st.table_stride;
+  const int R = min(nr * g, NW * 32);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5, col = lane & 31;
+  const int qi = wave * 32 + col;
+  const bool wave_has_rows = wave * 32 < R, qvalid = qi < R;
+  const int qrow = r0 + (qvalid ? qi / g : 0), qhead = hk * g + (qvalid ? qi % g : 0);
+
+  bf16x8 qf[8];
+  {
+    const bf16_t *qp = (const bf16_t *)a.q + (size_t)qrow * a.q_stride + (size_t)qhead * D + 8 * half;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      u32x4 v = qvalid ? *(const u32x4 *)(qp + 16 * ks) : (u32x4){0, 0, 0, 0};
+      qf[ks] = __builtin_bit_cast(bf16x8, v);
+    }
+  }
+
+  // staging of one K tile and one V^T tile (16 KB each, contiguous in the page)
+  int sk[CPT], sv[CPT];
+#pragma unroll
+  for (int i = 0; i < CPT; ++i) {
+    int c = tid + NT * i;
+    int tok = c >> 4, ch = c & 15;
+    sk[i] = tok * 256 + ((((ch & 7) ^ kkey(tok)) | (ch & 8)) << 4);
+    int d = c >> 3, cv = c & 7;
+    sv[i] = d * 128 + ((cv ^ (d & 7)) << 4);
+  }
+  const size_t page_bytes = (size_t)2 * Hkv * P * D * 2;
+  const unsigned char *pool = (const unsigned char *)a.kv.base;
+  const size_t k_head = (size_t)hk * P * D * 2, v_head = ((size_t)Hkv * P * D + (size_t)hk * D * P) * 2;
+  const int tile0 = t0 / 64, tile1 = (t1 + 63) / 64;
+  u32x4 rk[CPT], rv[CPT];
+  {
+    const unsigned char *pg = pool + (size_t)pt[tile0] * page_bytes;
+#pragma unroll
+    for (int i = 0; i < CPT; ++i) {
+      rk[i] = *(const u32x4 *)(pg + k_head + (size_t)(tid + NT * i) * 16);
+      rv[i] = *(const u32x4 *)(pg + v_head + (size_t)(tid + NT * i) * 16);
+    }
+  }
+
+  f32x16 oacc[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[i][r] = 0.f;
+  float m = -INFINITY, l = 0.f;
+  const float sc = 1.4426950408889634f / sqrtf((float)D);      // scores in the log2 domain
+
+  for (int tile = tile0; tile < tile1; ++tile) {
+#pragma unroll
+    for (int i = 0; i < CPT; ++i) {
+      *(u32x4 *)(Ks + sk[i]) = rk[i];
+      *(u32x4 *)(Vs + sv[i]) = rv[i];
+    }
+    __syncthreads();
+    {
+      const unsigned char *pg = pool + (size_t)pt[min(tile + 1, tile1 - 1)] * page_bytes;
+#pragma unroll
+      for (int i = 0; i < CPT; ++i) {
+        rk[i] = *(const u32x4 *)(pg + k_head + (size_t)(tid + NT * i) * 16);
+        rv[i] = *(const u32x4 *)(pg + v_head + (size_t)(tid + NT * i) * 16);
+      }
+    }
+    if (wave_has_rows) {
+      f32x16 sacc[2];
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sacc[u][r] = 0.f;
+        const int tl = 32 * u + sigma32(col), key = kkey(tl);
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+          const int ch = 2 * ks + half;
+          bf16x8 kf = *(const bf16x8 *)(Ks + tl * 256 + ((((ch & 7) ^ key) | (ch & 8)) << 4));
+          sacc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc[u], 0, 0, 0);
+        }
+      }
+      // scale, mask, running max
+      const bool need_mask = tile * 64 + 64 > L;
+      float mx = -INFINITY;
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float s = sacc[u][r] * sc;
+          if (need_mask) {
+            const int tok = tile * 64 + 32 * u + sigma32(8 * (r >> 2) + 4 * half + (r & 3));
+            const bool ok = tok < L || (tok < total && ((vis >> (tok - L)) & 1ull));
+            s = ok ? s : -INFINITY;
+          }
+          sacc[u][r] = s;
+          mx = fmaxf(mx, s);
+        }
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float m_new = fmaxf(m, mx);
+      const float m_use = m_new == -INFINITY ? 0.f : m_new;
+      const float corr = exp2f(m - m_use);
+      m = m_new;
+      float ls = 0.f;
+      bf16x8 pf[4];
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float p = exp2f(sacc[u][r] - m_use);
+          ls += p;
+          pf[2 * u + (r >> 3)][r & 7] = (bf16_t)p;
+        }
+      l = l * corr + ls;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[i][r] *= corr;
+#pragma unroll
+      for (int ds = 0; ds < 4; ++ds) {
+        const int vr = 32 * ds + col;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+          bf16x8 vf = *(const bf16x8 *)(Vs + vr * 128 + (((2 * kk + half) ^ (vr & 7)) << 4));
+          oacc[ds] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kk], oacc[ds], 0, 0, 0);
+        }
+      }
+    }
+    __syncthreads();
+  }
+
+  if (!qvalid) return;
+  const float l_tot = l + __shfl_xor(l, 32);
+  if (nsplit == 1) {
+    const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+    bf16_t *orow = (bf16_t *)a.out + (size_t)qrow * Hq * D + (size_t)qhead * D;
+#pragma unroll
+    for (int ds = 0; ds < 4; ++ds)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        bf16x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = (bf16_t)(oacc[ds][4 * q4 + e] * inv);
+        *(bf16x4 *)(orow + 32 * ds + 8 * q4 + 4 * half) = v;
+      }
   } else {
-    if (ne == 1) k_attn_rowwave<bf16_t, 1><<<grid, 64, 0, s>>>((const bf16_t *)q, q_stride, n_q_heads, rows, ri, st, vis_by_b, kv, (bf16_t *)out);
-    else k_attn_rowwave<bf16_t, 2><<<grid, 64, 0, s>>>((const bf16_t *)q, q_stride, n_q_heads, rows, ri, st, vis_by_b, kv, (bf16_t *)out);
+    const size_t pi = ((size_t)qrow * Hq + qhead) * a.max_splits + split;
+    float *po = a.part_o + pi * D;
+#pragma unroll
+    for (int ds = 0; ds < 4; ++ds)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        float4 v = make_float4(oacc[ds][4 * q4], oacc[ds][4 * q4 + 1], oacc[ds][4 * q4 + 2], oacc[ds][4 * q4 + 3]);
+        *(float4 *)(po + 32 * ds + 8 * q4 + 4 * half) = v;
+      }
+    if (half == 0) {
+      a.part_ml[pi * 2] = m;
+      a.part_ml[pi * 2 + 1] = l_tot;
+    }
+  }
+}
+
+// Merge of the K/V splits of one (row, head): out = sum_s o_s 2^(m_s - M) / sum_s l_s 2^(m_s - M), in split order.
+__global__ __launch_bounds__(128) void k_attn_combine(AttnArgs a) {
+  const int r = blockIdx.x, hq = blockIdx.y, d = threadIdx.x;
+  const int M = a.rows.count ? min(*a.rows.count, a.rows.cap) : a.rows.cap;
+  if (r >= M) return;
+  const int b = a.ri.row_map[r] / a.ri.B;
+  const int slot = slot_of(a.ri.seq_slot, b, a.st);
+  const int total = a.st.prefix_len[slot] + a.ri.B;
+  const int nsplit = (total + a.chunk - 1) / a.chunk;
+  if (nsplit <= 1) return;
+  const size_t pi = ((size_t)r * a.n_q_heads + hq) * a.max_splits;
+  float mm = -INFINITY;
+  for (int s = 0; s < nsplit; ++s) mm = fmaxf(mm, a.part_ml[(pi + s) * 2]);
+  float num = 0.f, den = 0.f;
+  for (int s = 0; s < nsplit; ++s) {
+    const float ms = a.part_ml[(pi + s) * 2];
+    const float w = ms == -INFINITY ? 0.f : exp2f(ms - mm);
+    num += a.part_o[(pi + s) * 128 + d] * w;
+    den += a.part_ml[(pi + s) * 2 + 1] * w;
+  }
+  ((bf16_t *)a.out)[((size_t)r * a.n_q_heads + hq) * 128 + d] = (bf16_t)(den > 0.f ? num / den : 0.f);
+}
+
+void attention(hipStream_t s, const AttnArgs &a) {
+  if (a.rows.cap <= 0 || a.n_seq <= 0) return;
+  const int g = a.n_q_heads / a.kv.n_kv_heads;
+  const bool mfma = a.dtype == FOCUS_BF16 && a.kv.head_dim == 128 && a.kv.page_size == 64 && a.max_rows_per_seq * g <= 256 &&
+                    a.q_stride % 8 == 0 && a.part_o != nullptr;
+  if (mfma) {
+    dim3 grid(a.n_seq * a.kv.n_kv_heads, a.launch_splits);
+    const int R = a.max_rows_per_seq * g;
+    if (R <= 32) k_attn_mfma<1><<<grid, 64, 0, s>>>(a);
+    else if (R <= 64) k_attn_mfma<2><<<grid, 128, 0, s>>>(a);
+    else if (R <= 128) k_attn_mfma<4><<<grid, 256, 0, s>>>(a);
+    else k_attn_mfma<8><<<grid, 512, 0, s>>>(a);
+    if (a.launch_splits > 1) k_attn_combine<<<dim3(a.rows.cap, a.n_q_heads), 128, 0, s>>>(a);
+    return;
+  }
+  dim3 grid(a.rows.cap, a.n_q_heads);
+  const int ne = a.kv.head_dim / 64;
+  if (a.dtype == FOCUS_F32) {
+    if (ne == 1) k_attn_rowwave<float, 1><<<grid, 64, 0, s>>>((const float *)a.q, a.q_stride, a.n_q_heads, a.rows, a.ri, a.st, a.vis_by_b, a.kv, (float *)a.out);
+    else k_attn_rowwave<float, 2><<<grid, 64, 0, s>>>((const float *)a.q, a.q_stride, a.n_q_heads, a.rows, a.ri, a.st, a.vis_by_b, a.kv, (float *)a.out);
+  } else {
+    if (ne == 1) k_attn_rowwave<bf16_t, 1><<<grid, 64, 0, s>>>((const bf16_t *)a.q, a.q_stride, a.n_q_heads, a.rows, a.ri, a.st, a.vis_by_b, a.kv, (bf16_t *)a.out);
+    else k_attn_rowwave<bf16_t, 2><<<grid, 64, 0, s>>>((const bf16_t *)a.q, a.q_stride, a.n_q_heads, a.rows, a.ri, a.st, a.vis_by_b, a.kv, (bf16_t *)a.out);
   }
 }
 

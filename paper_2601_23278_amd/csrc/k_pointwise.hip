@@ -111,7 +111,7 @@ __global__ __launch_bounds__(256) void k_rope_kv_write(T *qkv, int Hq, Rows rows
   T *vc = cache + (size_t)Hkv * P * D;
   for (int i = threadIdx.x; i < Hkv * D; i += 256) {
     int h = i / D, d = i % D;
-    vc[((size_t)h * P + off) * D + d] = v[i];
+    vc[((size_t)h * D + d) * P + off] = v[i];       // V is kept transposed: [H_kv][D][page_size]
   }
 }
 

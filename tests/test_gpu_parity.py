@@ -188,8 +188,11 @@ def test_c1_tiny_fp32_four_steps_exact():
         for b, st in enumerate(states):
             for t in range(st.prefix_len):
                 pg = pool.layers[l][st.pages[t // wl.page_size]]
-                got = kv[l, st.pages[t // wl.page_size], :, :, t % wl.page_size, :]
-                assert relerr(got, pg[:, :, t % wl.page_size, :]) <= 1e-3, (l, b, t)
+                page = kv[l, st.pages[t // wl.page_size]]
+                got_k = page[0][:, t % wl.page_size, :]
+                got_v = page[1].reshape(wl.n_kv_heads, wl.head_dim, wl.page_size)[:, :, t % wl.page_size]
+                assert relerr(got_k, pg[0, :, t % wl.page_size, :]) <= 1e-3, (l, b, t)
+                assert relerr(got_v, pg[1, :, t % wl.page_size, :]) <= 1e-3, (l, b, t)
     sess.focus.focus_free()
     stats = compare_steps(wl, wl.steps, 1e-3, exact=True)
     assert len(stats) == 4 and all(s["T"] == 16 for s in stats)

@@ -38,7 +38,8 @@ def test_fill_matches_values_and_page_view():
     assert sum(len(t) for t in tables) == n_pages and all(len(t) * wl.page_size >= l + wl.block_size for t, l in zip(tables, lens))
     pool = torch.empty((wl.n_layers, n_pages, 2, wl.n_kv_heads, wl.page_size, wl.head_dim))
     wl.kv_pool_fill_(pool)
-    assert torch.equal(pool[1, 3], wl.kv_page(1, 3, n_pages))
+    page = wl.kv_page(1, 3, n_pages)
+    assert torch.equal(pool[1, 3, 0], page[0]) and torch.equal(pool[1, 3, 1].reshape(wl.n_kv_heads, wl.head_dim, wl.page_size).transpose(1, 2), page[1])
     w = wl.layer_weight(1, "w_o")
     assert w.shape == (256, 256) and abs(float(w.std()) - 0.02) < 1e-3
 
