@@ -6,6 +6,8 @@
 //                does not take.
 //   k_gemm_mfma  bf16 on the matrix cores (see below).
 // M is read from device memory when the row count is only known on the device (packed batch after eviction).
+#include <stdlib.h>
+
 #include "focus_internal.h"
 
 namespace fk {
@@ -77,7 +79,7 @@ static void launch_valu(hipStream_t s, const void *A, const void *W, int N, int 
 // feed the instruction the same way: lane l supplies row l % 32, eight consecutive k starting at 8 * (l / 32).
 //
 // LDS holds one K-slab of each operand, rows of 64 bf16 = 128 B = eight 16-byte chunks; chunk c of row r is
-// stored at chunk position c ^ (r & 7), so the 32 rows read by one ds_read_b128 spread over all banks and
+// stored at chunk position c ^ ((r >> 1) & 7), so the 32 rows read by one ds_read_b128 spread over all banks and
 // the 8 lanes that fill a row write distinct chunks.  The next K-slab is fetched from global memory into
 // registers while the current one is multiplied (two workgroups per CU overlap each other's barriers).
 //
@@ -88,7 +90,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-template <int BM, int BN, int EPI>
+template <int BM, int BN, int EPI, bool PIPE>
 __global__ __launch_bounds__(256, 2) void k_gemm_mfma(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W, int N, int K,
                                                       Rows rows, void *out, int ldo, int tiles_m, int tiles_n) {
   constexpr int BK = 64, WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
@@ -118,13 +120,13 @@ __global__ __launch_bounds__(256, 2) void k_gemm_mfma(const bf16_t *__restrict__
   for (int i = 0; i < CA; ++i) {
     int c = tid + 256 * i, r = c >> 3, ch = c & 7;
     ga[i] = A + (size_t)min(m0 + r, M - 1) * K + ch * 8;
-    sa[i] = r * 128 + ((ch ^ (r & 7)) << 4);
+    sa[i] = r * 128 + ((ch ^ ((r >> 1) & 7)) << 4);
   }
 #pragma unroll
   for (int i = 0; i < CB; ++i) {
     int c = tid + 256 * i, r = c >> 3, ch = c & 7;
     gb[i] = W + (size_t)min(n0 + r, N - 1) * K + ch * 8;
-    sb[i] = r * 128 + ((ch ^ (r & 7)) << 4);
+    sb[i] = r * 128 + ((ch ^ ((r >> 1) & 7)) << 4);
   }
   u32x4 ra[CA], rb[CB];
 #pragma unroll
@@ -157,23 +159,50 @@ __global__ __launch_bounds__(256, 2) void k_gemm_mfma(const bf16_t *__restrict__
 #pragma unroll
       for (int i = 0; i < CB; ++i) rb[i] = *(const u32x4 *)(gb[i] + koff);
     }
+    if (PIPE) {
+      // fragments of K-step ks + 1 are read while the products of step ks issue
+      bf16x8 af[2][TM], bfr[2][TN];
+      auto load_frags = [&](int ks, bf16x8 *fa, bf16x8 *fb) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+          int r = wm + i * 32 + frow;
+          fa[i] = *(const bf16x8 *)(As + r * 128 + (((2 * ks + fch) ^ ((r >> 1) & 7)) << 4));
+        }
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          int r = wn + j * 32 + frow;
+          fb[j] = *(const bf16x8 *)(Bs + r * 128 + (((2 * ks + fch) ^ ((r >> 1) & 7)) << 4));
+        }
+      };
+      load_frags(0, af[0], bfr[0]);
+#pragma unroll
+      for (int ks = 0; ks < BK / 16; ++ks) {
+        if (ks + 1 < BK / 16) load_frags(ks + 1, af[(ks + 1) & 1], bfr[(ks + 1) & 1]);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr[ks & 1][j], acc[i][j], 0, 0, 0);
+      }
+    } else {
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
       bf16x8 af[TM], bfr[TN];
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
         int r = wm + i * 32 + frow;
-        af[i] = *(const bf16x8 *)(As + r * 128 + (((2 * ks + fch) ^ (r & 7)) << 4));
+        af[i] = *(const bf16x8 *)(As + r * 128 + (((2 * ks + fch) ^ ((r >> 1) & 7)) << 4));
       }
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
         int r = wn + j * 32 + frow;
-        bfr[j] = *(const bf16x8 *)(Bs + r * 128 + (((2 * ks + fch) ^ (r & 7)) << 4));
+        bfr[j] = *(const bf16x8 *)(Bs + r * 128 + (((2 * ks + fch) ^ ((r >> 1) & 7)) << 4));
       }
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    }
     }
     __syncthreads();
   }
@@ -192,14 +221,20 @@ __global__ __launch_bounds__(256, 2) void k_gemm_mfma(const bf16_t *__restrict__
     }
 }
 
-template <int BM, int BN>
+template <int BM, int BN, bool PIPE>
 static void launch_mfma(hipStream_t s, const void *A, const void *W, int N, int K, Rows rows, int epi, void *out, int ldo) {
   const int tiles_m = (rows.cap + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   const int grid = ((tiles_m * tiles_n + 7) / 8) * 8;
   const bf16_t *a = (const bf16_t *)A, *w = (const bf16_t *)W;
-  if (epi == EPI_STORE) k_gemm_mfma<BM, BN, EPI_STORE><<<grid, 256, 0, s>>>(a, w, N, K, rows, out, ldo, tiles_m, tiles_n);
-  else if (epi == EPI_ADD_F32) k_gemm_mfma<BM, BN, EPI_ADD_F32><<<grid, 256, 0, s>>>(a, w, N, K, rows, out, ldo, tiles_m, tiles_n);
-  else k_gemm_mfma<BM, BN, EPI_STORE_F32><<<grid, 256, 0, s>>>(a, w, N, K, rows, out, ldo, tiles_m, tiles_n);
+  if (epi == EPI_STORE) k_gemm_mfma<BM, BN, EPI_STORE, PIPE><<<grid, 256, 0, s>>>(a, w, N, K, rows, out, ldo, tiles_m, tiles_n);
+  else if (epi == EPI_ADD_F32) k_gemm_mfma<BM, BN, EPI_ADD_F32, PIPE><<<grid, 256, 0, s>>>(a, w, N, K, rows, out, ldo, tiles_m, tiles_n);
+  else k_gemm_mfma<BM, BN, EPI_STORE_F32, PIPE><<<grid, 256, 0, s>>>(a, w, N, K, rows, out, ldo, tiles_m, tiles_n);
+}
+
+static int gemm_variant() {
+  static int v = -1;
+  if (v < 0) { const char *e = getenv("FOCUS_GEMM_VARIANT"); v = e ? atoi(e) : 0; }
+  return v;
 }
 
 void gemm(hipStream_t s, int dtype, const void *A, const void *W, int N, int K, Rows rows, int epilogue,
@@ -208,7 +243,12 @@ void gemm(hipStream_t s, int dtype, const void *A, const void *W, int N, int K, 
   if (dtype == FOCUS_F32) { launch_valu<float>(s, A, W, N, K, rows, epilogue, out, ldo); return; }
   const bool aligned = K % 64 == 0 && ((uintptr_t)A & 15) == 0 && ((uintptr_t)W & 15) == 0;
   if (!aligned) { launch_valu<bf16_t>(s, A, W, N, K, rows, epilogue, out, ldo); return; }
-  launch_mfma<256, 128>(s, A, W, N, K, rows, epilogue, out, ldo);
+  switch (gemm_variant()) {
+    case 1: launch_mfma<128, 128, false>(s, A, W, N, K, rows, epilogue, out, ldo); break;
+    case 2: launch_mfma<256, 128, true>(s, A, W, N, K, rows, epilogue, out, ldo); break;
+    case 3: launch_mfma<128, 128, true>(s, A, W, N, K, rows, epilogue, out, ldo); break;
+    default: launch_mfma<256, 128, false>(s, A, W, N, K, rows, epilogue, out, ldo); break;
+  }
 }
 
 }  // namespace fk
