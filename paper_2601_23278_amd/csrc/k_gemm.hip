@@ -6,8 +6,6 @@
 //                does not take.
 //   k_gemm_mfma  bf16 on the matrix cores (see below).
 // M is read from device memory when the row count is only known on the device (packed batch after eviction).
-#include <stdlib.h>
-
 #include "focus_internal.h"
 
 namespace fk {
@@ -90,7 +88,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-template <int BM, int BN, int EPI, bool PIPE>
+template <int BM, int BN, int EPI>
 __global__ __launch_bounds__(256, 2) void k_gemm_mfma(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W, int N, int K,
                                                       Rows rows, void *out, int ldo, int tiles_m, int tiles_n) {
   constexpr int BK = 64, WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
@@ -159,32 +157,6 @@ __global__ __launch_bounds__(256, 2) void k_gemm_mfma(const bf16_t *__restrict__
 #pragma unroll
       for (int i = 0; i < CB; ++i) rb[i] = *(const u32x4 *)(gb[i] + koff);
     }
-    if (PIPE) {
-      // fragments of K-step ks + 1 are read while the products of step ks issue
-      bf16x8 af[2][TM], bfr[2][TN];
-      auto load_frags = [&](int ks, bf16x8 *fa, bf16x8 *fb) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-          int r = wm + i * 32 + frow;
-          fa[i] = *(const bf16x8 *)(As + r * 128 + (((2 * ks + fch) ^ ((r >> 1) & 7)) << 4));
-        }
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          int r = wn + j * 32 + frow;
-          fb[j] = *(const bf16x8 *)(Bs + r * 128 + (((2 * ks + fch) ^ ((r >> 1) & 7)) << 4));
-        }
-      };
-      load_frags(0, af[0], bfr[0]);
-#pragma unroll
-      for (int ks = 0; ks < BK / 16; ++ks) {
-        if (ks + 1 < BK / 16) load_frags(ks + 1, af[(ks + 1) & 1], bfr[(ks + 1) & 1]);
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int j = 0; j < TN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr[ks & 1][j], acc[i][j], 0, 0, 0);
-      }
-    } else {
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
       bf16x8 af[TM], bfr[TN];
@@ -203,7 +175,6 @@ __global__ __launch_bounds__(256, 2) void k_gemm_mfma(const bf16_t *__restrict__
 #pragma unroll
         for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
     }
-    }
     __syncthreads();
   }
 
@@ -221,20 +192,14 @@ __global__ __launch_bounds__(256, 2) void k_gemm_mfma(const bf16_t *__restrict__
     }
 }
 
-template <int BM, int BN, bool PIPE>
+template <int BM, int BN>
 static void launch_mfma(hipStream_t s, const void *A, const void *W, int N, int K, Rows rows, int epi, void *out, int ldo) {
   const int tiles_m = (rows.cap + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   const int grid = ((tiles_m * tiles_n + 7) / 8) * 8;
   const bf16_t *a = (const bf16_t *)A, *w = (const bf16_t *)W;
-  if (epi == EPI_STORE) k_gemm_mfma<BM, BN, EPI_STORE, PIPE><<<grid, 256, 0, s>>>(a, w, N, K, rows, out, ldo, tiles_m, tiles_n);
-  else if (epi == EPI_ADD_F32) k_gemm_mfma<BM, BN, EPI_ADD_F32, PIPE><<<grid, 256, 0, s>>>(a, w, N, K, rows, out, ldo, tiles_m, tiles_n);
-  else k_gemm_mfma<BM, BN, EPI_STORE_F32, PIPE><<<grid, 256, 0, s>>>(a, w, N, K, rows, out, ldo, tiles_m, tiles_n);
-}
-
-static int gemm_variant() {
-  static int v = -1;
-  if (v < 0) { const char *e = getenv("FOCUS_GEMM_VARIANT"); v = e ? atoi(e) : 0; }
-  return v;
+  if (epi == EPI_STORE) k_gemm_mfma<BM, BN, EPI_STORE><<<grid, 256, 0, s>>>(a, w, N, K, rows, out, ldo, tiles_m, tiles_n);
+  else if (epi == EPI_ADD_F32) k_gemm_mfma<BM, BN, EPI_ADD_F32><<<grid, 256, 0, s>>>(a, w, N, K, rows, out, ldo, tiles_m, tiles_n);
+  else k_gemm_mfma<BM, BN, EPI_STORE_F32><<<grid, 256, 0, s>>>(a, w, N, K, rows, out, ldo, tiles_m, tiles_n);
 }
 
 void gemm(hipStream_t s, int dtype, const void *A, const void *W, int N, int K, Rows rows, int epilogue,
@@ -243,12 +208,10 @@ void gemm(hipStream_t s, int dtype, const void *A, const void *W, int N, int K, 
   if (dtype == FOCUS_F32) { launch_valu<float>(s, A, W, N, K, rows, epilogue, out, ldo); return; }
   const bool aligned = K % 64 == 0 && ((uintptr_t)A & 15) == 0 && ((uintptr_t)W & 15) == 0;
   if (!aligned) { launch_valu<bf16_t>(s, A, W, N, K, rows, epilogue, out, ldo); return; }
-  switch (gemm_variant()) {
-    case 1: launch_mfma<128, 128, false>(s, A, W, N, K, rows, epilogue, out, ldo); break;
-    case 2: launch_mfma<256, 128, true>(s, A, W, N, K, rows, epilogue, out, ldo); break;
-    case 3: launch_mfma<128, 128, true>(s, A, W, N, K, rows, epilogue, out, ldo); break;
-    default: launch_mfma<256, 128, false>(s, A, W, N, K, rows, epilogue, out, ldo); break;
-  }
+  // 256x128 tiles when they still give every CU two workgroups, 128x128 tiles below that
+  const long tiles_big = (long)((rows.cap + 255) / 256) * ((N + 127) / 128);
+  if (tiles_big >= 512) launch_mfma<256, 128>(s, A, W, N, K, rows, epilogue, out, ldo);
+  else launch_mfma<128, 128>(s, A, W, N, K, rows, epilogue, out, ldo);
 }
 
 }  // namespace fk
