@@ -209,8 +209,13 @@ void layer_rest(focus_ctx *c, hipStream_t s, int l, const RowSet &rs, float *res
     fk::attention(s, a); }
   { Timed t(c, s, FOCUS_KC_GEMM); fk::gemm(s, g.dtype, attn, c->w_o[l], g.hidden, q_w, rs.rows, fk::EPI_ADD_F32, resid, g.hidden); }
   { Timed t(c, s, FOCUS_KC_POINTWISE); fk::rmsnorm(s, g.dtype, resid, c->mlp_norm[l], normed, g.hidden, g.rms_eps, rs.rows); }
-  { Timed t(c, s, FOCUS_KC_GEMM); fk::gemm(s, g.dtype, normed, c->w_gate_up[l], 2 * g.ffn, g.hidden, rs.rows, fk::EPI_STORE, gate_up, 2 * g.ffn); }
-  { Timed t(c, s, FOCUS_KC_POINTWISE); fk::silu_mul(s, g.dtype, gate_up, act, g.ffn, rs.rows); }
+  if (fk::gemm_fuses_silu_mul(g.dtype, normed, c->w_gate_up[l], 2 * g.ffn, g.hidden)) {
+    Timed t(c, s, FOCUS_KC_GEMM);
+    fk::gemm(s, g.dtype, normed, c->w_gate_up[l], 2 * g.ffn, g.hidden, rs.rows, fk::EPI_SILU_MUL, act, g.ffn);
+  } else {
+    { Timed t(c, s, FOCUS_KC_GEMM); fk::gemm(s, g.dtype, normed, c->w_gate_up[l], 2 * g.ffn, g.hidden, rs.rows, fk::EPI_STORE, gate_up, 2 * g.ffn); }
+    { Timed t(c, s, FOCUS_KC_POINTWISE); fk::silu_mul(s, g.dtype, gate_up, act, g.ffn, rs.rows); }
+  }
   { Timed t(c, s, FOCUS_KC_GEMM); fk::gemm(s, g.dtype, act, c->w_down[l], g.hidden, g.ffn, rs.rows, fk::EPI_ADD_F32, resid, g.hidden); }
 }
 

@@ -54,7 +54,13 @@ struct KvLayer {
   int page_size, n_kv_heads, head_dim;
 };
 
-enum Epilogue { EPI_STORE = 0 /* out[dtype] = acc */, EPI_ADD_F32 = 1 /* out[f32] += acc */, EPI_STORE_F32 = 2 };
+enum Epilogue {
+  EPI_STORE = 0,     // out[dtype] = acc
+  EPI_ADD_F32 = 1,   // out[f32] += acc
+  EPI_STORE_F32 = 2, // out[f32] = acc
+  EPI_SILU_MUL = 3   // W = [gate rows; up rows] (N = 2F): out[dtype][m, f] = silu(gate) * up; only where gemm_fuses_silu_mul()
+};
+bool gemm_fuses_silu_mul(int dtype, const void *A, const void *W, int N, int K);
 
 void embed(hipStream_t s, int dtype, const void *table, int hidden, Rows rows, RowIndex ri, SlotState st,
            int mask_id, float *resid);

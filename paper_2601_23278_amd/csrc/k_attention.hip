@@ -8,6 +8,7 @@
 namespace fk {
 
 template <typename T> __device__ __forceinline__ float to_f(T v) { return (float)v; }
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float wave_sum(float v) {
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
@@ -78,7 +79,6 @@ __global__ __launch_bounds__(64) void k_attn_rowwave(const T *__restrict__ q, in
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ int sigma32(int i) { return (i & ~12) | ((i & 4) << 1) | ((i & 8) >> 1); }
 __device__ __forceinline__ int kkey(int token) { return (token & 3) | (((token >> 3) & 1) << 2); }
@@ -331,12 +331,18 @@ __global__ __launch_bounds__(256) void k_importance(const T *__restrict__ qkv, i
     float acc[MAXB / 4];
     for (int jj = 0; jj < MAXB / 4; ++jj) acc[jj] = 0.f;
     const T *qi = base + (size_t)i * stride + (size_t)h * D;
-    for (int d = 0; d < D; ++d) {
-      float qd = to_f(qi[d]);
+    constexpr int VE = 16 / sizeof(T);            // the query row is read in 16-byte pieces
+    for (int d0 = 0; d0 < D; d0 += VE) {
+      T qv[VE];
+      *(u32x4 *)qv = *(const u32x4 *)(qi + d0);
 #pragma unroll
-      for (int jj = 0; jj < MAXB / 4; ++jj) {
-        int j = j0 + 4 * jj;
-        if (j < B) acc[jj] += qd * ks[j * (D + 1) + d];
+      for (int e = 0; e < VE; ++e) {
+        const float qd = to_f(qv[e]);
+#pragma unroll
+        for (int jj = 0; jj < MAXB / 4; ++jj) {
+          int j = j0 + 4 * jj;
+          if (j < B) acc[jj] += qd * ks[j * (D + 1) + d0 + e];
+        }
       }
     }
 #pragma unroll

@@ -105,8 +105,9 @@ __global__ __launch_bounds__(256, 2) void k_gemm_mfma(const bf16_t *__restrict__
   constexpr int GROUP = 8;
   const int in_group = tile % (GROUP * tiles_n), first_m = (tile / (GROUP * tiles_n)) * GROUP;
   const int gsz = min(tiles_m - first_m, GROUP);
-  const int m0 = (first_m + in_group % gsz) * BM, n0 = (in_group / gsz) * BN;
+  const int m0 = (first_m + in_group % gsz) * BM, n0 = (in_group / gsz) * (EPI == EPI_SILU_MUL ? BN / 2 : BN);
   if (m0 >= M) return;
+  static_assert(EPI != EPI_SILU_MUL || BN == 128, "the fused SiLU*up epilogue pairs the two column tiles of a wavefront");
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = (wave >> 1) * WM, wn = (wave & 1) * WN;
@@ -123,7 +124,11 @@ __global__ __launch_bounds__(256, 2) void k_gemm_mfma(const bf16_t *__restrict__
 #pragma unroll
   for (int i = 0; i < CB; ++i) {
     int c = tid + 256 * i, r = c >> 3, ch = c & 7;
-    gb[i] = W + (size_t)min(n0 + r, N - 1) * K + ch * 8;
+    // fused SiLU*up: the two 32-column accumulator tiles of a wavefront are the gate and the up projection of
+    // the same 32 activation columns, so LDS row r holds gate row n0 + ... for even 32-row groups and the
+    // matching up row (F rows further) for odd ones
+    const int wrow = EPI == EPI_SILU_MUL ? ((r >> 5) & 1) * (N / 2) + n0 + (r / WN) * 32 + (r & 31) : n0 + r;
+    gb[i] = W + (size_t)min(wrow, N - 1) * K + ch * 8;
     sb[i] = r * 128 + ((ch ^ ((r >> 1) & 7)) << 4);
   }
   u32x4 ra[CA], rb[CB];
@@ -179,6 +184,18 @@ __global__ __launch_bounds__(256, 2) void k_gemm_mfma(const bf16_t *__restrict__
   }
 
   // epilogue: accumulator register r of lane l is C[8 * (r / 4) + 4 * (l / 32) + r % 4][l % 32] of its 32x32 tile
+  if (EPI == EPI_SILU_MUL) {
+    const int gn = n0 + (wn / WN) * 32 + (lane & 31);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int gm = m0 + wm + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        const float g = acc[i][0][r], u = acc[i][TN - 1][r];
+        if (gm < M && gn < N / 2) ((bf16_t *)out)[(size_t)gm * ldo + gn] = (bf16_t)(g / (1.0f + __expf(-g)) * u);
+      }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -194,12 +211,18 @@ __global__ __launch_bounds__(256, 2) void k_gemm_mfma(const bf16_t *__restrict__
 
 template <int BM, int BN>
 static void launch_mfma(hipStream_t s, const void *A, const void *W, int N, int K, Rows rows, int epi, void *out, int ldo) {
-  const int tiles_m = (rows.cap + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+  const int tiles_m = (rows.cap + BM - 1) / BM;
+  const int tiles_n = epi == EPI_SILU_MUL ? (N / 2 + BN / 2 - 1) / (BN / 2) : (N + BN - 1) / BN;
   const int grid = ((tiles_m * tiles_n + 7) / 8) * 8;
   const bf16_t *a = (const bf16_t *)A, *w = (const bf16_t *)W;
-  if (epi == EPI_STORE) k_gemm_mfma<BM, BN, EPI_STORE><<<grid, 256, 0, s>>>(a, w, N, K, rows, out, ldo, tiles_m, tiles_n);
+  if (epi == EPI_SILU_MUL) k_gemm_mfma<BM, BN, EPI_SILU_MUL><<<grid, 256, 0, s>>>(a, w, N, K, rows, out, ldo, tiles_m, tiles_n);
+  else if (epi == EPI_STORE) k_gemm_mfma<BM, BN, EPI_STORE><<<grid, 256, 0, s>>>(a, w, N, K, rows, out, ldo, tiles_m, tiles_n);
   else if (epi == EPI_ADD_F32) k_gemm_mfma<BM, BN, EPI_ADD_F32><<<grid, 256, 0, s>>>(a, w, N, K, rows, out, ldo, tiles_m, tiles_n);
   else k_gemm_mfma<BM, BN, EPI_STORE_F32><<<grid, 256, 0, s>>>(a, w, N, K, rows, out, ldo, tiles_m, tiles_n);
+}
+
+bool gemm_fuses_silu_mul(int dtype, const void *A, const void *W, int N, int K) {
+  return dtype == FOCUS_BF16 && K % 64 == 0 && N % 2 == 0 && ((uintptr_t)A & 15) == 0 && ((uintptr_t)W & 15) == 0;
 }
 
 void gemm(hipStream_t s, int dtype, const void *A, const void *W, int N, int K, Rows rows, int epilogue,

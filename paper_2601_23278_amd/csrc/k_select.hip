@@ -161,11 +161,19 @@ __global__ __launch_bounds__(256) void k_confidence(const float *__restrict__ lo
   const int M = rows.count ? min(*rows.count, rows.cap) : rows.cap;
   if (r >= M) return;
   const float *x = logits + (size_t)r * vocab;
+  const int nv = ((size_t)x & 15) == 0 ? vocab / 4 : 0;       // 16-byte pieces when the row is aligned
   float m = -INFINITY;
   int mi = 0x7fffffff;
-  for (int i = threadIdx.x; i < vocab; i += 256) {
+  for (int i = threadIdx.x; i < nv; i += 256) {
+    const float4 v = ((const float4 *)x)[i];
+    if (v.x > m) { m = v.x; mi = 4 * i; }          // ascending index per lane: the first maximum is kept
+    if (v.y > m) { m = v.y; mi = 4 * i + 1; }
+    if (v.z > m) { m = v.z; mi = 4 * i + 2; }
+    if (v.w > m) { m = v.w; mi = 4 * i + 3; }
+  }
+  for (int i = 4 * nv + threadIdx.x; i < vocab; i += 256) {
     float v = x[i];
-    if (v > m) { m = v; mi = i; }               // ascending i per lane: first maximum is kept
+    if (v > m) { m = v; mi = i; }
   }
   for (int o = 32; o > 0; o >>= 1) {
     float om = __shfl_xor(m, o);
@@ -179,7 +187,11 @@ __global__ __launch_bounds__(256) void k_confidence(const float *__restrict__ lo
   for (int i = 1; i < 4; ++i)
     if (smax[i] > m || (smax[i] == m && sidx[i] < mi)) { m = smax[i]; mi = sidx[i]; }
   float sum = 0.f;
-  for (int i = threadIdx.x; i < vocab; i += 256) sum += __expf(x[i] - m);
+  for (int i = threadIdx.x; i < nv; i += 256) {
+    const float4 v = ((const float4 *)x)[i];
+    sum += __expf(v.x - m) + __expf(v.y - m) + __expf(v.z - m) + __expf(v.w - m);
+  }
+  for (int i = 4 * nv + threadIdx.x; i < vocab; i += 256) sum += __expf(x[i] - m);
   for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
   if ((threadIdx.x & 63) == 0) ssum[w] = sum;
   __syncthreads();
