@@ -4,6 +4,7 @@
 #include <stdarg.h>
 #include <stdio.h>
 #include <string.h>
+#include <stdlib.h>
 
 #include <new>
 
@@ -21,7 +22,7 @@ struct Plan {
   size_t off_rope, off_resid, off_resid_p, off_normed, off_qkv, off_q_p, off_attn, off_gate_up, off_act, off_logits;
   size_t off_partial, off_delta, off_K, off_keep, off_n_keep, off_vis, off_cu, off_cu_full, off_row_map,
       off_row_map_full, off_total, off_total_full, off_conf, off_argmax, off_prompt, off_prompt_off, off_prompt_len,
-      off_slot_list, off_part_o, off_part_ml;
+      off_slot_list, off_part_o, off_part_ml, off_order;
   size_t bytes, part_entries;
   int table_stride, max_rows, max_pos;
 };
@@ -77,6 +78,7 @@ Plan make_plan(const focus_config &c) {
   p.part_entries = c.dtype == FOCUS_BF16 ? (size_t)B * (c.n_q_heads / c.n_kv_heads) * kTargetAttnGroups + rows * c.n_q_heads : 0;
   p.off_part_o = take(p.part_entries * c.head_dim * 4);
   p.off_part_ml = take(p.part_entries * 2 * 4);
+  p.off_order = take(nb * 4);
   p.bytes = at;
   return p;
 }
@@ -172,6 +174,7 @@ struct RowSet {        // a set of rows the layers run on
   int n_seq;
   const int32_t *cu;   // rows of sequence b: cu[b] .. cu[b + 1]
   int max_rows_per_seq;
+  const int32_t *order;   // attention launch order (longest sequence first) or null
 };
 
 // K/V split size for the attention launch: whole sequences when there are enough (sequence, kv head) groups
@@ -204,6 +207,7 @@ void layer_rest(focus_ctx *c, hipStream_t s, int l, const RowSet &rs, float *res
     a.kv = c->kv_layer(l); a.out = attn;
     a.part_o = c->plan.part_entries ? c->at<float>(c->plan.off_part_o) : nullptr;
     a.part_ml = c->plan.part_entries ? c->at<float>(c->plan.off_part_ml) : nullptr;
+    a.order = rs.order;
     attention_split(c, rs.n_seq, rs.rows.cap, &a.chunk, &a.launch_splits);
     a.max_splits = a.launch_splits;
     fk::attention(s, a); }
@@ -226,6 +230,7 @@ void attention_split(const focus_ctx *c, int n_seq, int rows_cap, int *chunk, in
   long want = (groups >= kTargetAttnGroups) ? 1 : (kTargetAttnGroups + groups - 1) / groups;   // splits per sequence
   long ch = ((max_total + want - 1) / want + 63) / 64 * 64;
   if (ch < 256) ch = 256;
+  { static long force = -1; if (force < 0) { const char *e = getenv("FOCUS_ATTN_CHUNK"); force = e ? atol(e) : 0; } if (force > 0) ch = force; }
   // partial buffer: rows * H_q * splits entries
   while (c->plan.part_entries && (long)rows_cap * g.n_q_heads * ((max_total + ch - 1) / ch) > (long)c->plan.part_entries) ch *= 2;
   *chunk = (int)ch;
@@ -450,7 +455,7 @@ int focus_prefill_kv(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int3
     uint64_t *keep = ctx->at<uint64_t>(pl.off_keep);
     int32_t *cu = ctx->at<int32_t>(pl.off_cu), *row_map = ctx->at<int32_t>(pl.off_row_map), *total = ctx->at<int32_t>(pl.off_total);
     float *resid = ctx->at<float>(pl.off_resid_p);
-    RowSet rs{{n_seq * B, total}, {row_map, d_slots, B}, n_seq, cu, B};
+    RowSet rs{{n_seq * B, total}, {row_map, d_slots, B}, n_seq, cu, B, nullptr};
     const int qkv_w = (g.n_q_heads + 2 * g.n_kv_heads) * g.head_dim;
     for (int c0 = 0; c0 * B < max_len; ++c0) {
       fk::prefill_chunk_setup(s, n_seq, B, c0, d_slots, st, ctx->at<int32_t>(pl.off_prompt), d_off, d_len, keep);
@@ -498,9 +503,10 @@ int focus_step(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32_t *s
   float *logits = o.logits ? o.logits : ctx->at<float>(pl.off_logits);
 
   // phase 1: whole block through layers 0 .. e-1, layer e up to its K/V fill, importance of layers e-1 and e
-  RowSet full{{T0, nullptr}, {ctx->at<int32_t>(pl.off_row_map_full), seq_slot, B}, n_seq, ctx->at<int32_t>(pl.off_cu_full), B};
+  RowSet full{{T0, nullptr}, {ctx->at<int32_t>(pl.off_row_map_full), seq_slot, B}, n_seq, ctx->at<int32_t>(pl.off_cu_full), B, ctx->at<int32_t>(pl.off_order)};
   { Timed t(ctx, s, FOCUS_KC_POINTWISE);
     fk::iota_rows(s, ctx->at<int32_t>(pl.off_row_map_full), ctx->at<int32_t>(pl.off_cu_full), n_seq, B, ctx->at<int32_t>(pl.off_total_full));
+    fk::length_order(s, n_seq, seq_slot, st, ctx->at<int32_t>(pl.off_order));
     fk::embed(s, g.dtype, ctx->embed, g.hidden, full.rows, full.ri, st, g.mask_token_id, resid); }
   for (int l = 0; l < e; ++l) {
     layer_qkv(ctx, s, l, full, resid);
@@ -532,7 +538,7 @@ int focus_step(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32_t *s
     fk::scan_compact(s, n_seq, B, keep, cu, row_map, total);
   }
   const int cap = packed_cap(g, n_seq, keep_override != nullptr);
-  RowSet packed{{cap, total}, {row_map, seq_slot, B}, n_seq, cu, n_seq > 0 ? (cap + n_seq - 1) / n_seq : 0};
+  RowSet packed{{cap, total}, {row_map, seq_slot, B}, n_seq, cu, n_seq > 0 ? (cap + n_seq - 1) / n_seq : 0, ctx->at<int32_t>(pl.off_order)};
   { Timed t(ctx, s, FOCUS_KC_EVICT);
     fk::gather_rows(s, g.dtype, packed.rows, row_map, resid, resid_p, g.hidden, qkv, qkv_w, q_p, q_w); }
 

@@ -85,6 +85,8 @@ struct AttnArgs {
   void *out;                     // [rows, H_q * D]
   float *part_o, *part_ml;       // split-K/V partials: [rows, H_q, max_splits, D] and [.., 2]
   int chunk, max_splits, launch_splits;
+  int debug_skip;                // TEMP experiment knob
+  const int32_t *order;          // batch entries sorted by descending prefix length (longest first), or null
 };
 void attention(hipStream_t s, const AttnArgs &a);
 // Eq. 2 per (sequence, query head) on the full-block qkv buffer: partial[b, h, j].
@@ -138,5 +140,7 @@ void reset_block_state(hipStream_t s, int n_seq, int B, const int32_t *seq_slot,
                        const int32_t *prefix_len, int mask_id, int keep_stats);
 void fill_u64(hipStream_t s, uint64_t *p, int n, uint64_t v);
 void iota_rows(hipStream_t s, int32_t *row_map, int32_t *cu, int n_seq, int B, int32_t *total);
+// order[rank] = batch entry, ranked by descending prefix length (ties: lower entry first)
+void length_order(hipStream_t s, int n_seq, const int32_t *seq_slot, SlotState st, int32_t *order);
 
 }  // namespace fk

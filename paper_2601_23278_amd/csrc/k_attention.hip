@@ -3,6 +3,7 @@
 // A query row (sequence b, block position p) attends to the sequence's whole prefix [0, L) and to the
 // in-block positions whose bit is set in the sequence's visibility set (all B in the layers up to the
 // eviction layer; the processed positions above it).  There is no mask inside the block (Sec. 1-2).
+#include <stdlib.h>
 #include "focus_internal.h"
 
 namespace fk {
@@ -81,15 +82,21 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 __device__ __forceinline__ int sigma32(int i) { return (i & ~12) | ((i & 4) << 1) | ((i & 8) >> 1); }
-__device__ __forceinline__ int kkey(int token) { return (token & 3) | (((token >> 3) & 1) << 2); }
+
+// s_waitcnt immediate that waits for at most n outstanding vector-memory operations and for nothing else
+// (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8)
+constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
+
+#define FK_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
+#define FK_GLB_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
 
 template <int NW>
-__global__ __launch_bounds__(NW * 64) void k_attn_mfma(AttnArgs a) {
-  constexpr int D = 128, P = 64, NT = NW * 64, CPT = 1024 / NT;
-  __shared__ __attribute__((aligned(16))) unsigned char Ks[64 * 256];
-  __shared__ __attribute__((aligned(16))) unsigned char Vs[128 * 128];
+__global__ __launch_bounds__(NW * 64, 2) void k_attn_mfma(AttnArgs a) {
+  constexpr int D = 128, P = 64, IPW = 16 / NW;       // 1 KB load instructions per wavefront for K, and for V
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[32768];
   const int Hkv = a.kv.n_kv_heads, Hq = a.n_q_heads, g = Hq / Hkv;
-  const int b = blockIdx.x / Hkv, hk = blockIdx.x % Hkv, split = blockIdx.y;
+  const int bo = blockIdx.x / Hkv, hk = blockIdx.x % Hkv, split = blockIdx.y;
+  const int b = a.order ? a.order[bo] : bo;
   const int r0 = a.cu[b], nr = a.cu[b + 1] - r0;
   if (nr <= 0) return;
   const int slot = slot_of(a.ri.seq_slot, b, a.st);
@@ -103,7 +110,7 @@ __global__ __launch_bounds__(NW * 64) void k_attn_mfma(AttnArgs a) {
   const int R = min(nr * g, NW * 32);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5, col = lane & 31;
   const int qi = wave * 32 + col;
-  const bool wave_has_rows = wave * 32 < R, qvalid = qi < R;
+  const bool wave_has_rows = wave * 32 < R && !(a.debug_skip & 1), qvalid = qi < R;
   const int qrow = r0 + (qvalid ? qi / g : 0), qhead = hk * g + (qvalid ? qi % g : 0);
 
   bf16x8 qf[8];
@@ -116,29 +123,42 @@ __global__ __launch_bounds__(NW * 64) void k_attn_mfma(AttnArgs a) {
     }
   }
 
-  // staging of one K tile and one V^T tile (16 KB each, contiguous in the page)
-  int sk[CPT], sv[CPT];
-#pragma unroll
-  for (int i = 0; i < CPT; ++i) {
-    int c = tid + NT * i;
-    int tok = c >> 4, ch = c & 15;
-    sk[i] = tok * 256 + ((((ch & 7) ^ kkey(tok)) | (ch & 8)) << 4);
-    int d = c >> 3, cv = c & 7;
-    sv[i] = d * 128 + ((cv ^ (d & 7)) << 4);
-  }
+  // Tiles go from global memory straight into LDS (global_load_lds_dwordx4: lane l of an instruction fills
+  // the 16-byte slot l of a 1 KB LDS block), so the swizzle is applied on the global side: the lane that owns
+  // slot (row, position p) fetches the chunk that belongs there.  K block = 4 token rows x 16 chunks,
+  // chunk c of token t sits at position c ^ (t & 15); V^T block = 8 d rows x 8 chunks, chunk c of row d at
+  // position c ^ ((d >> 1) & 7).  Both make the 16 rows that one LDS read cycle serves hit 16 distinct
+  // 16-byte bank groups.
   const size_t page_bytes = (size_t)2 * Hkv * P * D * 2;
   const unsigned char *pool = (const unsigned char *)a.kv.base;
   const size_t k_head = (size_t)hk * P * D * 2, v_head = ((size_t)Hkv * P * D + (size_t)hk * D * P) * 2;
-  const int tile0 = t0 / 64, tile1 = (t1 + 63) / 64;
-  u32x4 rk[CPT], rv[CPT];
-  {
-    const unsigned char *pg = pool + (size_t)pt[tile0] * page_bytes;
+  int gk[IPW], gv[IPW];                                // per-lane byte offsets inside the K / V^T tile
 #pragma unroll
-    for (int i = 0; i < CPT; ++i) {
-      rk[i] = *(const u32x4 *)(pg + k_head + (size_t)(tid + NT * i) * 16);
-      rv[i] = *(const u32x4 *)(pg + v_head + (size_t)(tid + NT * i) * 16);
-    }
+  for (int q = 0; q < IPW; ++q) {
+    const int blk = wave * IPW + q;
+    const int tok = 4 * blk + (lane >> 4), pk = lane & 15;
+    gk[q] = tok * 256 + ((pk ^ (tok & 15)) << 4);
+    const int d = 8 * blk + (lane >> 3), pv = lane & 7;
+    gv[q] = d * 128 + ((pv ^ ((d >> 1) & 7)) << 4);
   }
+  unsigned char *const Ks = lds, *const Vs = lds + 16384;
+  // Page ids of the next 64 tiles are kept in one register (lane i = tile base + i) and broadcast with
+  // readlane, so a tile's loads never wait for a dependent page-table read.
+  const int tile0 = t0 / 64, tile1 = (t1 + 63) / 64;
+  int ptreg = pt[min(tile0 + lane, tile1 - 1)];
+  auto page_of = [&](int tile) { return (size_t)__builtin_amdgcn_readlane(ptreg, (tile - tile0) & 63); };
+  auto issue_k = [&](int tile) {
+    const unsigned char *pg = pool + page_of(tile) * page_bytes + k_head;
+#pragma unroll
+    for (int q = 0; q < IPW; ++q)
+      __builtin_amdgcn_global_load_lds(FK_GLB_PTR(pg + gk[q]), FK_LDS_PTR(Ks + (wave * IPW + q) * 1024), 16, 0, 0);
+  };
+  auto issue_v = [&](int tile) {
+    const unsigned char *pg = pool + page_of(tile) * page_bytes + v_head;
+#pragma unroll
+    for (int q = 0; q < IPW; ++q)
+      __builtin_amdgcn_global_load_lds(FK_GLB_PTR(pg + gv[q]), FK_LDS_PTR(Vs + (wave * IPW + q) * 1024), 16, 0, 0);
+  };
 
   f32x16 oacc[4];
 #pragma unroll
@@ -148,35 +168,40 @@ __global__ __launch_bounds__(NW * 64) void k_attn_mfma(AttnArgs a) {
   float m = -INFINITY, l = 0.f;
   const float sc = 1.4426950408889634f / sqrtf((float)D);      // scores in the log2 domain
 
+  // One K buffer and one V^T buffer, refilled as soon as the product that reads them is done: the K tile of
+  // the next step streams in during this step's softmax and P V product, the V tile during the next step's
+  // K Q^T product.  Loads complete in issue order, so "at most IPW outstanding" means the older tile landed.
+  issue_k(tile0);
+  issue_v(tile0);
   for (int tile = tile0; tile < tile1; ++tile) {
-#pragma unroll
-    for (int i = 0; i < CPT; ++i) {
-      *(u32x4 *)(Ks + sk[i]) = rk[i];
-      *(u32x4 *)(Vs + sv[i]) = rv[i];
-    }
-    __syncthreads();
-    {
-      const unsigned char *pg = pool + (size_t)pt[min(tile + 1, tile1 - 1)] * page_bytes;
-#pragma unroll
-      for (int i = 0; i < CPT; ++i) {
-        rk[i] = *(const u32x4 *)(pg + k_head + (size_t)(tid + NT * i) * 16);
-        rv[i] = *(const u32x4 *)(pg + v_head + (size_t)(tid + NT * i) * 16);
-      }
-    }
+    const bool more = tile + 1 < tile1;
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(IPW));          // K(tile) is in LDS
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    f32x16 sacc[2];
     if (wave_has_rows) {
-      f32x16 sacc[2];
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) sacc[u][r] = 0.f;
-        const int tl = 32 * u + sigma32(col), key = kkey(tl);
+        const int tl = 32 * u + sigma32(col);
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
           const int ch = 2 * ks + half;
-          bf16x8 kf = *(const bf16x8 *)(Ks + tl * 256 + ((((ch & 7) ^ key) | (ch & 8)) << 4));
+          bf16x8 kf = *(const bf16x8 *)(Ks + tl * 256 + ((ch ^ (tl & 15)) << 4));
           sacc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc[u], 0, 0, 0);
         }
       }
+    }
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();                        // every wavefront has read the K tile
+    if (more && ((tile + 1 - tile0) & 63) == 0) {        // next batch of page ids (drains the queue: once per 64 tiles)
+      ptreg = pt[min(tile + 1 + lane, tile1 - 1)];
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    }
+    if (more) issue_k(tile + 1);
+    bf16x8 pf[4];
+    if (wave_has_rows) {
       // scale, mask, running max
       const bool need_mask = tile * 64 + 64 > L;
       float mx = -INFINITY;
@@ -199,7 +224,6 @@ __global__ __launch_bounds__(NW * 64) void k_attn_mfma(AttnArgs a) {
       const float corr = exp2f(m - m_use);
       m = m_new;
       float ls = 0.f;
-      bf16x8 pf[4];
 #pragma unroll
       for (int u = 0; u < 2; ++u)
 #pragma unroll
@@ -213,17 +237,24 @@ __global__ __launch_bounds__(NW * 64) void k_attn_mfma(AttnArgs a) {
       for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[i][r] *= corr;
+    }
+    if (more) __builtin_amdgcn_s_waitcnt(vmcnt_imm(IPW)); else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));   // V(tile) is in LDS
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    if (wave_has_rows) {
 #pragma unroll
       for (int ds = 0; ds < 4; ++ds) {
         const int vr = 32 * ds + col;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
-          bf16x8 vf = *(const bf16x8 *)(Vs + vr * 128 + (((2 * kk + half) ^ (vr & 7)) << 4));
+          bf16x8 vf = *(const bf16x8 *)(Vs + vr * 128 + (((2 * kk + half) ^ ((vr >> 1) & 7)) << 4));
           oacc[ds] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kk], oacc[ds], 0, 0, 0);
         }
       }
     }
-    __syncthreads();
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();                        // every wavefront has read the V tile
+    if (more) issue_v(tile + 1);
   }
 
   if (!qvalid) return;
@@ -280,7 +311,9 @@ __global__ __launch_bounds__(128) void k_attn_combine(AttnArgs a) {
   ((bf16_t *)a.out)[((size_t)r * a.n_q_heads + hq) * 128 + d] = (bf16_t)(den > 0.f ? num / den : 0.f);
 }
 
-void attention(hipStream_t s, const AttnArgs &a) {
+void attention(hipStream_t s, const AttnArgs &a0) {
+  AttnArgs a = a0;
+  { static int dbg = -1; if (dbg < 0) { const char *e = getenv("FOCUS_ATTN_DEBUG"); dbg = e ? atoi(e) : 0; } a.debug_skip = dbg; }
   if (a.rows.cap <= 0 || a.n_seq <= 0) return;
   const int g = a.n_q_heads / a.kv.n_kv_heads;
   const bool mfma = a.dtype == FOCUS_BF16 && a.kv.head_dim == 128 && a.kv.page_size == 64 && a.max_rows_per_seq * g <= 256 &&

@@ -194,6 +194,23 @@ void iota_rows(hipStream_t s, int32_t *row_map, int32_t *cu, int n_seq, int B, i
   k_iota_rows<<<(n_seq * B + 256) / 256, 256, 0, s>>>(row_map, cu, n_seq, B, total);
 }
 
+// Longest-first launch order for the attention workgroups: with a handful of workgroups per CU and an 8x
+// spread of prefix lengths, starting the long sequences first keeps the tail of the launch short.
+__global__ __launch_bounds__(256) void k_length_order(int n_seq, const int32_t *seq_slot, SlotState st, int32_t *order) {
+  const int b = blockIdx.x * 256 + threadIdx.x;
+  if (b >= n_seq) return;
+  const int len = st.prefix_len[slot_of(seq_slot, b, st)];
+  int rank = 0;
+  for (int o = 0; o < n_seq; ++o) {
+    const int lo = st.prefix_len[slot_of(seq_slot, o, st)];
+    rank += (lo > len || (lo == len && o < b)) ? 1 : 0;
+  }
+  order[rank] = b;
+}
+void length_order(hipStream_t s, int n_seq, const int32_t *seq_slot, SlotState st, int32_t *order) {
+  if (n_seq > 0) k_length_order<<<(n_seq + 255) / 256, 256, 0, s>>>(n_seq, seq_slot, st, order);
+}
+
 // New block: every position masked, nothing processed; statistics kept or cleared.
 __global__ void k_reset_block(int n_seq, int B, const int32_t *seq_slot, SlotState st, const int32_t *prefix_len,
                               int mask_id, int keep_stats) {
