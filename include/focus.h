@@ -156,6 +156,17 @@ int focus_step(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32_t *s
 int focus_select_compact(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32_t *seq_slot,
                          const float *delta_I, const int32_t *k_override, const focus_step_out *out);
 
+/* Stage entry: runs layers [layer_begin, layer_end) of the reduced forward pass (Alg. 1 phase 3, "Forward(H_reduced,
+ * C, Layers = 1_suffix ... L)") on caller-given hidden states, so that deep layers can be compared with a
+ * reference fed the same input.  layer_begin must be above the eviction layer.  Rows are the positions in
+ * keep_bits, packed as focus_step packs them; their K/V in those layers is rewritten; in-block keys visible to the
+ * attention are vis_bits.  The slot state is not changed.
+ *   keep_bits, vis_bits  device [n_seq]
+ *   hidden               device [T', hidden] fp32, residual stream entering layer_begin; overwritten with the
+ *                        residual stream leaving layer_end - 1 */
+int focus_run_layers(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32_t *seq_slot, const uint64_t *keep_bits,
+                     const uint64_t *vis_bits, int32_t layer_begin, int32_t layer_end, float *hidden);
+
 /* Stage entry: confidence-based commit (Alg. 1 Decode_and_Verify, App. E.3.1 statistics) on caller-given
  * confidences.  Updates the slot state and writes out->tokens, mask_bits, n_decoded.
  *   keep_bits     device [n_seq]; cu_seqlens device [n_seq + 1]; conf, argmax device [cu_seqlens[n_seq]] */

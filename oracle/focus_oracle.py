@@ -377,6 +377,7 @@ class StepTrace:
     row_map: List[int] = field(default_factory=list)
     hidden_full: Optional[np.ndarray] = None                   # [n*B, h] residual stream entering layer e
     hidden_packed: Optional[np.ndarray] = None                 # [T', h] residual stream after the last layer
+    hidden_entering: Dict[int, np.ndarray] = field(default_factory=dict)   # layer l > e -> [T', h] stream entering it
     logits: Optional[np.ndarray] = None                        # [T', V]
     conf: Optional[np.ndarray] = None
     argmax: Optional[np.ndarray] = None
@@ -387,7 +388,7 @@ class StepTrace:
 def focus_step(cfg: OracleConfig, W: Weights, pool: KVPool, seqs: List[SeqState],
                k_override: Optional[Sequence[int]] = None,
                keep_override: Optional[Sequence[Sequence[int]]] = None,
-               score_cast=None, conf_cast=None) -> StepTrace:
+               score_cast=None, conf_cast=None, record_layers=None) -> StepTrace:
     """One FOCUS inference step (Alg. 1) for a batch of sequences, in place on `seqs` and `pool`.
 
     Order of work, as in Alg. 1 and App. C: layers below the eviction layer e run on the whole
@@ -401,7 +402,8 @@ def focus_step(cfg: OracleConfig, W: Weights, pool: KVPool, seqs: List[SeqState]
 
     keep_override: per-sequence retained sets to use instead of budget()+select() (teacher forcing).
     score_cast / conf_cast: optional functions applied to the delta and to the confidences before
-    the integer decisions (e.g. rounding to float32 so both sides decide in the same precision)."""
+    the integer decisions (e.g. rounding to float32 so both sides decide in the same precision).
+    record_layers: layers (> e) whose incoming residual stream is kept in the trace."""
     B, e = cfg.block_size, cfg.evict_layer
     n = len(seqs)
     tr = StepTrace()
@@ -473,6 +475,8 @@ def focus_step(cfg: OracleConfig, W: Weights, pool: KVPool, seqs: List[SeqState]
 
     # layers e+1 .. on the retained rows
     for l in range(e + 1, cfg.n_layers):
+        if record_layers is not None and l in record_layers:
+            tr.hidden_entering[l] = Xp.copy()
         w = W.layer(l)
         abs_pos = np.array([seqs[r // B].prefix_len + r % B for r in tr.row_map], dtype=np.int64)
         q, k, v = _project_qkv(cfg, w, Xp, abs_pos)

@@ -70,6 +70,7 @@ def load_library() -> C.CDLL:
         "focus_step": [P, P, I, P, P, P, C.POINTER(focus_step_out)],
         "focus_select_compact": [P, P, I, P, P, P, C.POINTER(focus_step_out)],
         "focus_commit": [P, P, I, P, P, P, P, P, C.POINTER(focus_step_out)],
+        "focus_run_layers": [P, P, I, P, P, P, I, I, P],
         "focus_get_state": [P, I, C.POINTER(focus_seq_state)],
         "focus_set_state": [P, I, C.POINTER(focus_seq_state)],
         "focus_set_timing": [P, I],
@@ -85,7 +86,7 @@ def load_library() -> C.CDLL:
 
 _lib = load_library()
 EXPORTS = ["focus_workspace_bytes", "focus_kv_pool_bytes", "focus_init", "focus_prefill_kv", "focus_step",
-           "focus_select_compact", "focus_commit", "focus_get_state", "focus_set_state", "focus_set_timing",
+           "focus_select_compact", "focus_commit", "focus_run_layers", "focus_get_state", "focus_set_state", "focus_set_timing",
            "focus_get_kernel_time", "focus_free", "focus_last_error"]
 
 
@@ -173,6 +174,11 @@ class Focus:
                      stream=None):
         _check(_lib.focus_commit(self._ctx, self._stream(stream), n_seq, _ptr(seq_slot), _ptr(keep_bits), _ptr(cu_seqlens),
                                  _ptr(conf), _ptr(argmax), None if out is None else C.byref(out)), self._ctx)
+
+    def focus_run_layers(self, n_seq: int, keep_bits: torch.Tensor, vis_bits: torch.Tensor, layer_begin: int,
+                         layer_end: int, hidden: torch.Tensor, seq_slot: Optional[torch.Tensor] = None, stream=None):
+        _check(_lib.focus_run_layers(self._ctx, self._stream(stream), n_seq, _ptr(seq_slot), _ptr(keep_bits), _ptr(vis_bits),
+                                     layer_begin, layer_end, _ptr(hidden)), self._ctx)
 
     def focus_get_state(self, slot: int) -> focus_seq_state:
         st = focus_seq_state()

@@ -588,6 +588,32 @@ int focus_select_compact(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const 
   return FOCUS_OK;
 }
 
+int focus_run_layers(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32_t *seq_slot, const uint64_t *keep_bits,
+                     const uint64_t *vis_bits, int32_t layer_begin, int32_t layer_end, float *hidden) {
+  if (int rc = check_batch(ctx, n_seq)) return rc;
+  if (!keep_bits || !vis_bits || !hidden) return fail(ctx, FOCUS_EINVAL, "null argument");
+  const focus_config &g = ctx->cfg;
+  if (layer_begin <= g.evict_layer || layer_end > g.n_layers || layer_begin > layer_end)
+    return fail(ctx, FOCUS_EINVAL, "layers [%d, %d) must lie in (evict_layer, n_layers]", layer_begin, layer_end);
+  if (n_seq == 0) return FOCUS_OK;
+  const Plan &pl = ctx->plan;
+  hipStream_t s = (hipStream_t)hip_stream;
+  const int B = g.block_size, cap = n_seq * B;
+  const int qkv_w = (g.n_q_heads + 2 * g.n_kv_heads) * g.head_dim;
+  int32_t *cu = ctx->at<int32_t>(pl.off_cu), *row_map = ctx->at<int32_t>(pl.off_row_map), *total = ctx->at<int32_t>(pl.off_total);
+  float *resid_p = ctx->at<float>(pl.off_resid_p);
+  fk::scan_compact(s, n_seq, B, keep_bits, cu, row_map, total);
+  HIP_TRY(ctx, hipMemcpyAsync(resid_p, hidden, (size_t)cap * g.hidden * 4, hipMemcpyDeviceToDevice, s));
+  RowSet packed{{cap, total}, {row_map, seq_slot, B}, n_seq, cu, B, nullptr};
+  for (int l = layer_begin; l < layer_end; ++l) {
+    layer_qkv(ctx, s, l, packed, resid_p);
+    layer_rest(ctx, s, l, packed, resid_p, ctx->at<char>(pl.off_qkv), qkv_w, vis_bits);
+  }
+  HIP_TRY(ctx, hipMemcpyAsync(hidden, resid_p, (size_t)cap * g.hidden * 4, hipMemcpyDeviceToDevice, s));
+  HIP_TRY(ctx, hipGetLastError());
+  return FOCUS_OK;
+}
+
 int focus_commit(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32_t *seq_slot, const uint64_t *keep_bits,
                  const int32_t *cu_seqlens, const float *conf, const int32_t *argmax, const focus_step_out *out) {
   if (int rc = check_batch(ctx, n_seq)) return rc;
