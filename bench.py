@@ -100,8 +100,10 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debug only; the JSON says so)")
     ap.add_argument("--batch", type=int, default=0, help="override the batch (debug only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-seqs", type=int, default=4)
-    ap.add_argument("--cpu-layers", type=int, default=5)
+    ap.add_argument("--cpu-seqs", type=int, default=32)
+    ap.add_argument("--cpu-layers", type=int, default=6)
+    ap.add_argument("--pmc-calibrate", action="store_true",
+                    help="also launch one 1 GiB device-to-device copy (a dispatch of known size for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (sequences are independent; see DESIGN.md for how the "
@@ -173,11 +175,23 @@ def main():
     achieved = flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
     kvb = kv_bytes_per_step(wl, sess.prefix_lens)
     attn_ms = classes["attention"]["ms"]
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "pmc_traffic_%s_keep%03d.json" % (wl.name, int(round(1000 * args.keep_ratio))))
+    if os.path.exists(tpath) and not (args.layers or args.batch):
+        traffic = json.load(open(tpath)).get("gemm_hbm_bytes_per_step")
     roofline = dict(bound="mfma", kernel="gemm (all dense projections of a step)", achieved=round(achieved, 2), peak=PEAK_BF16_TFLOPS,
-                    unit="TFLOP/s", frac=round(achieved / PEAK_BF16_TFLOPS, 4), traffic=None,
+                    unit="TFLOP/s", frac=round(achieved / PEAK_BF16_TFLOPS, 4), traffic=traffic,
                     flops_per_step=flops, launches=classes["gemm"]["launches"], avg_launch_ms=round(gemm_ms / max(1, classes["gemm"]["launches"]), 5))
     attention = dict(bound="hbm", achieved=round(kvb / (attn_ms * 1e-3) / 1e9, 1) if attn_ms > 0 else 0.0, peak=PEAK_HBM_GBS, unit="GB/s",
                      frac=round(kvb / (attn_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4) if attn_ms > 0 else 0.0, kv_bytes_per_step=kvb)
+
+    if args.pmc_calibrate:
+        a_ = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")
+        b_ = torch.empty_like(a_)
+        a_.fill_(1)
+        torch.cuda.synchronize()
+        b_.copy_(a_)
+        torch.cuda.synchronize()
 
     sweep = None
     if args.sweep:

@@ -4,7 +4,6 @@
 #include <stdarg.h>
 #include <stdio.h>
 #include <string.h>
-#include <stdlib.h>
 
 #include <new>
 
@@ -230,7 +229,6 @@ void attention_split(const focus_ctx *c, int n_seq, int rows_cap, int *chunk, in
   long want = (groups >= kTargetAttnGroups) ? 1 : (kTargetAttnGroups + groups - 1) / groups;   // splits per sequence
   long ch = ((max_total + want - 1) / want + 63) / 64 * 64;
   if (ch < 256) ch = 256;
-  { static long force = -1; if (force < 0) { const char *e = getenv("FOCUS_ATTN_CHUNK"); force = e ? atol(e) : 0; } if (force > 0) ch = force; }
   // partial buffer: rows * H_q * splits entries
   while (c->plan.part_entries && (long)rows_cap * g.n_q_heads * ((max_total + ch - 1) / ch) > (long)c->plan.part_entries) ch *= 2;
   *chunk = (int)ch;

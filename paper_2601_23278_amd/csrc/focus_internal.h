@@ -85,7 +85,6 @@ struct AttnArgs {
   void *out;                     // [rows, H_q * D]
   float *part_o, *part_ml;       // split-K/V partials: [rows, H_q, max_splits, D] and [.., 2]
   int chunk, max_splits, launch_splits;
-  int debug_skip;                // TEMP experiment knob
   const int32_t *order;          // batch entries sorted by descending prefix length (longest first), or null
 };
 void attention(hipStream_t s, const AttnArgs &a);

@@ -3,7 +3,6 @@
 // A query row (sequence b, block position p) attends to the sequence's whole prefix [0, L) and to the
 // in-block positions whose bit is set in the sequence's visibility set (all B in the layers up to the
 // eviction layer; the processed positions above it).  There is no mask inside the block (Sec. 1-2).
-#include <stdlib.h>
 #include "focus_internal.h"
 
 namespace fk {
@@ -110,7 +109,7 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_mfma(AttnArgs a) {
   const int R = min(nr * g, NW * 32);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5, col = lane & 31;
   const int qi = wave * 32 + col;
-  const bool wave_has_rows = wave * 32 < R && !(a.debug_skip & 1), qvalid = qi < R;
+  const bool wave_has_rows = wave * 32 < R, qvalid = qi < R;
   const int qrow = r0 + (qvalid ? qi / g : 0), qhead = hk * g + (qvalid ? qi % g : 0);
 
   bf16x8 qf[8];
@@ -311,9 +310,7 @@ __global__ __launch_bounds__(128) void k_attn_combine(AttnArgs a) {
   ((bf16_t *)a.out)[((size_t)r * a.n_q_heads + hq) * 128 + d] = (bf16_t)(den > 0.f ? num / den : 0.f);
 }
 
-void attention(hipStream_t s, const AttnArgs &a0) {
-  AttnArgs a = a0;
-  { static int dbg = -1; if (dbg < 0) { const char *e = getenv("FOCUS_ATTN_DEBUG"); dbg = e ? atoi(e) : 0; } a.debug_skip = dbg; }
+void attention(hipStream_t s, const AttnArgs &a) {
   if (a.rows.cap <= 0 || a.n_seq <= 0) return;
   const int g = a.n_q_heads / a.kv.n_kv_heads;
   const bool mfma = a.dtype == FOCUS_BF16 && a.kv.head_dim == 128 && a.kv.page_size == 64 && a.max_rows_per_seq * g <= 256 &&
