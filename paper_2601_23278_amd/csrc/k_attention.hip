@@ -414,10 +414,96 @@ __global__ __launch_bounds__(256) void k_importance(const T *__restrict__ qkv, i
   }
 }
 
+// bf16, D = 128: the same reduction on the matrix cores, one wavefront per (sequence, query head).
+// S^T = K Q^T puts a query row in each lane (both lane halves hold the row of query l % 32 after one exchange),
+// so pooling, max, exp and normalisation run in registers; the column sums are 5-step lane reductions, the lower
+// lane half finishing the lower half of the keys and the upper half the rest.
+template <int NJ>   // key tiles of 32: B <= 32 * NJ
+__global__ __launch_bounds__(64) void k_importance_mfma(const bf16_t *__restrict__ qkv, int B, int Hq, int Hkv, int pool_k,
+                                                        float *partial) {
+  constexpr int D = 128, BJ = 32 * NJ, HJ = BJ / 2;
+  const int b = blockIdx.x, h = blockIdx.y, hk = h / (Hq / Hkv);
+  const int lane = threadIdx.x, half = lane >> 5, col = lane & 31;
+  const int stride = (Hq + 2 * Hkv) * D;
+  const bf16_t *base = qkv + (size_t)b * B * stride;
+  const float sc = 1.4426950408889634f / sqrtf((float)D);
+  bf16x8 kf[NJ][8];
+#pragma unroll
+  for (int jt = 0; jt < NJ; ++jt) {
+    const bf16_t *kp = base + (size_t)min(32 * jt + col, B - 1) * stride + (size_t)(Hq + hk) * D + 8 * half;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) kf[jt][ks] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(kp + 16 * ks));
+  }
+  float acc[HJ];
+#pragma unroll
+  for (int jj = 0; jj < HJ; ++jj) acc[jj] = 0.f;
+
+  for (int it = 0; it * 32 < B; ++it) {
+    const int i = 32 * it + col;
+    bf16x8 qf[8];
+    const bf16_t *qp = base + (size_t)min(i, B - 1) * stride + (size_t)h * D + 8 * half;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qf[ks] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(qp + 16 * ks));
+    // full score row of query i in every lane: own registers for the keys of this lane half, the partner's for the rest
+    float row[BJ];
+#pragma unroll
+    for (int jt = 0; jt < NJ; ++jt) {
+      f32x16 sacc;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[jt][ks], qf[ks], sacc, 0, 0, 0);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float mine = sacc[r] * sc, other = __shfl_xor(mine, 32);
+        const int j0 = 32 * jt + 8 * (r >> 2) + (r & 3);          // key of register r in lane half 0; half 1 holds j0 + 4
+        row[j0] = half ? other : mine;
+        row[j0 + 4] = half ? mine : other;
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < BJ; ++j) row[j] = j < B ? row[j] : -INFINITY;
+    float pooled[BJ], m = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < BJ; ++j) {
+      float v = row[j];
+      if (pool_k == 3) {
+        if (j > 0) v = fmaxf(v, row[j - 1]);
+        if (j + 1 < BJ) v = fmaxf(v, row[j + 1]);
+      }
+      pooled[j] = v;
+      m = fmaxf(m, v);
+    }
+    float sum = 0.f;
+#pragma unroll
+    for (int j = 0; j < BJ; ++j) {
+      pooled[j] = exp2f(pooled[j] - m);
+      sum += pooled[j];
+    }
+    const float inv = i < B ? 1.0f / sum : 0.f;                   // rows beyond the block add nothing
+#pragma unroll
+    for (int jj = 0; jj < HJ; ++jj) {
+      float v = (half ? pooled[jj + HJ] : pooled[jj]) * inv;
+      for (int o = 16; o > 0; o >>= 1) v += __shfl_xor(v, o);     // over the 32 queries of this lane half
+      acc[jj] += v;
+    }
+  }
+#pragma unroll
+  for (int jj = 0; jj < HJ; ++jj) {
+    const int j = half * HJ + jj;
+    if (col == (jj & 31) && j < B) partial[((size_t)b * Hq + h) * B + j] = acc[jj];
+  }
+}
+
 void importance(hipStream_t s, int dtype, const void *qkv, int n_seq, int B, int n_q_heads, int n_kv_heads,
                 int head_dim, int maxpool_k, float *partial) {
   if (n_seq <= 0) return;
   dim3 grid(n_seq, n_q_heads);
+  if (dtype == FOCUS_BF16 && head_dim == 128 && ((uintptr_t)qkv & 15) == 0) {
+    if (B <= 32) k_importance_mfma<1><<<grid, 64, 0, s>>>((const bf16_t *)qkv, B, n_q_heads, n_kv_heads, maxpool_k, partial);
+    else k_importance_mfma<2><<<grid, 64, 0, s>>>((const bf16_t *)qkv, B, n_q_heads, n_kv_heads, maxpool_k, partial);
+    return;
+  }
   if (dtype == FOCUS_F32)
     k_importance<float, 64, 128><<<grid, 256, 0, s>>>((const float *)qkv, B, n_q_heads, n_kv_heads, head_dim, maxpool_k, partial);
   else
