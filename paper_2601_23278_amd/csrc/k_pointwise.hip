@@ -68,8 +68,49 @@ __global__ __launch_bounds__(256) void k_rmsnorm(const float *x, const T *w, T *
   }
 }
 
+// bf16 output, hidden <= 8192: the row is read once (kept in registers between the two phases) and written
+// as 16-byte vectors.
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+__global__ __launch_bounds__(256) void k_rmsnorm_bf16(const float *x, const bf16_t *w, bf16_t *y, int hidden, float eps, Rows rows) {
+  __shared__ float sh[4];
+  const int r = blockIdx.x;
+  if (r >= n_rows(rows)) return;
+  const float *xr = x + (size_t)r * hidden;
+  float v[4][8];
+  float ss = 0.f;
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int i = (it * 256 + threadIdx.x) * 8;
+    if (i < hidden) {
+      const float4 a = *(const float4 *)(xr + i), b = *(const float4 *)(xr + i + 4);
+      v[it][0] = a.x; v[it][1] = a.y; v[it][2] = a.z; v[it][3] = a.w;
+      v[it][4] = b.x; v[it][5] = b.y; v[it][6] = b.z; v[it][7] = b.w;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) ss += v[it][e] * v[it][e];
+    }
+  }
+  ss = block_sum_256(ss, sh);
+  const float inv = 1.0f / sqrtf(ss / (float)hidden + eps);
+  bf16_t *yr = y + (size_t)r * hidden;
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int i = (it * 256 + threadIdx.x) * 8;
+    if (i < hidden) {
+      const bf16x8_t wv = *(const bf16x8_t *)(w + i);
+      bf16x8_t o;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e] = (bf16_t)(v[it][e] * inv * (float)wv[e]);
+      *(bf16x8_t *)(yr + i) = o;
+    }
+  }
+}
+
 void rmsnorm(hipStream_t s, int dtype, const float *x, const void *w, void *y, int hidden, float eps, Rows rows) {
   if (rows.cap <= 0) return;
+  if (dtype == FOCUS_BF16 && hidden % 8 == 0 && hidden <= 8192 && (((uintptr_t)x | (uintptr_t)w | (uintptr_t)y) & 15) == 0) {
+    k_rmsnorm_bf16<<<rows.cap, 256, 0, s>>>(x, (const bf16_t *)w, (bf16_t *)y, hidden, eps, rows);
+    return;
+  }
   if (dtype == FOCUS_F32)
     k_rmsnorm<float><<<rows.cap, 256, 0, s>>>(x, (const float *)w, (float *)y, hidden, eps, rows);
   else
@@ -115,9 +156,49 @@ __global__ __launch_bounds__(256) void k_rope_kv_write(T *qkv, int Hq, Rows rows
   }
 }
 
+// bf16: eight rotation pairs per thread step, 16-byte loads and stores (q, k in place; k also into its cache row).
+__global__ __launch_bounds__(256) void k_rope_kv_write_bf16(bf16_t *qkv, int Hq, Rows rows, RowIndex ri, SlotState st, KvLayer kv,
+                                                            const float2 *rope) {
+  const int r = blockIdx.x;
+  if (r >= n_rows(rows)) return;
+  const int D = kv.head_dim, half = D / 2, Hkv = kv.n_kv_heads, P = kv.page_size, upr = half / 8;   // units per head
+  const int rm = ri.row_map[r], b = rm / ri.B, p = rm % ri.B;
+  const int slot = slot_of(ri.seq_slot, b, st);
+  const int pos = st.prefix_len[slot] + p;
+  const int page = st.page_table[(size_t)slot * st.table_stride + pos / P], off = pos % P;
+  bf16_t *row = qkv + (size_t)r * (Hq + 2 * Hkv) * D;
+  bf16_t *cache = (bf16_t *)kv.base + (size_t)page * 2 * Hkv * P * D;
+  const float2 *cs = rope + (size_t)pos * half;
+  for (int u = threadIdx.x; u < (Hq + Hkv) * upr; u += 256) {
+    const int h = u / upr, d = (u % upr) * 8;
+    bf16x8_t x1 = *(const bf16x8_t *)(row + h * D + d), x2 = *(const bf16x8_t *)(row + h * D + d + half), y1, y2;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float2 c = cs[d + e];
+      const float a = (float)x1[e], bb = (float)x2[e];
+      y1[e] = (bf16_t)(a * c.x - bb * c.y);
+      y2[e] = (bf16_t)(bb * c.x + a * c.y);
+    }
+    *(bf16x8_t *)(row + h * D + d) = y1;
+    *(bf16x8_t *)(row + h * D + d + half) = y2;
+    if (h >= Hq) {
+      bf16_t *dst = cache + ((size_t)(h - Hq) * P + off) * D;
+      *(bf16x8_t *)(dst + d) = y1;
+      *(bf16x8_t *)(dst + d + half) = y2;
+    }
+  }
+  const bf16_t *v = row + (size_t)(Hq + Hkv) * D;
+  bf16_t *vc = cache + (size_t)Hkv * P * D;
+  for (int i = threadIdx.x; i < Hkv * D; i += 256) vc[(size_t)i * P + off] = v[i];   // V transposed: [H_kv][D][page_size]
+}
+
 void rope_kv_write(hipStream_t s, int dtype, void *qkv, int n_q_heads, Rows rows, RowIndex ri, SlotState st,
                    KvLayer kv, const float2 *rope_table) {
   if (rows.cap <= 0) return;
+  if (dtype == FOCUS_BF16 && kv.head_dim % 16 == 0 && (((uintptr_t)qkv | (uintptr_t)kv.base) & 15) == 0) {
+    k_rope_kv_write_bf16<<<rows.cap, 256, 0, s>>>((bf16_t *)qkv, n_q_heads, rows, ri, st, kv, rope_table);
+    return;
+  }
   if (dtype == FOCUS_F32)
     k_rope_kv_write<float><<<rows.cap, 256, 0, s>>>((float *)qkv, n_q_heads, rows, ri, st, kv, rope_table);
   else
