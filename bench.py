@@ -100,7 +100,7 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debug only; the JSON says so)")
     ap.add_argument("--batch", type=int, default=0, help="override the batch (debug only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-seqs", type=int, default=32)
+    ap.add_argument("--cpu-seqs", type=int, default=96)
     ap.add_argument("--cpu-layers", type=int, default=6)
     ap.add_argument("--pmc-calibrate", action="store_true",
                     help="also launch one 1 GiB device-to-device copy (a dispatch of known size for scaling rocprofv3 byte counters)")
