@@ -528,3 +528,35 @@ def prefill(cfg: OracleConfig, W: Weights, pool: KVPool, seqs: List[SeqState], p
                     pool.write(l, st.pages, c0 + i, k[i], v[i])
                 Kc, Vc = pool.read(l, st.pages, list(range(c0 + len(blk))))
                 X = _finish_layer(cfg, w, X, _attention(cfg, q, Kc, Vc))
+
+
+def finalize_blocks(cfg: OracleConfig, W: Weights, pool: KVPool, seqs: List[SeqState]) -> List[bool]:
+    """Multi-block generation (the engine loop around Alg. 1, App. E.3.1 "state persistence and reset"): a
+    sequence whose block has no masked position left gets one last forward of the whole block with its
+    committed tokens through every layer, so that the K/V the block leaves behind is the exact K/V of those
+    tokens (each saw the final tokens of its block); then the block becomes part of the prefix
+    (prefix_len += B) and a new all-masked block starts.  The running statistics persist.  Sequences that
+    still have masked positions, or whose page list has no room for another block, are left untouched.
+    Returns which sequences were finalized."""
+    B = cfg.block_size
+    done = []
+    for st in seqs:
+        room = (st.prefix_len + 2 * B) <= len(st.pages) * cfg.page_size
+        if any(st.masked) or not room:
+            done.append(False)
+            continue
+        X = W.embed[np.array(st.tokens)]
+        pos = st.prefix_len + np.arange(B)
+        for l in range(cfg.n_layers):
+            w = W.layer(l)
+            q, k, v = _project_qkv(cfg, w, X, pos)
+            for p in range(B):
+                pool.write(l, st.pages, st.prefix_len + p, k[p], v[p])
+            Kc, Vc = pool.read(l, st.pages, list(range(st.prefix_len + B)))
+            X = _finish_layer(cfg, w, X, _attention(cfg, q, Kc, Vc))
+        st.prefix_len += B
+        st.tokens = [cfg.mask_token_id] * B
+        st.masked = [True] * B
+        st.processed = [False] * B
+        done.append(True)
+    return done

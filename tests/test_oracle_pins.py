@@ -538,3 +538,62 @@ def test_override_budget_zero_and_full():
     assert tr.cu == [0, 0, 8, 11]
     assert states[0].total_steps == 0 and states[0].token_sum == 0 and tr.n_decoded[0] == 0
     assert states[1].total_steps == 1 and tr.n_decoded[1] == 1
+
+
+# ---------------------------------------------------------------------------------------------
+# multi-block generation: finalized blocks leave the exact K/V of their tokens
+
+@pytest.mark.parametrize("keep_ratio", [1.0, 0.25])
+def test_finalized_block_kv_equals_prefill_of_the_generated_tokens(keep_ratio):
+    cfg = tiny_cfg(n_layers=3, keep_ratio=keep_ratio)
+    W = tiny_weights(cfg, seed=21)
+    B = cfg.block_size
+    lens = [8, 16]                                                # block-aligned prefixes
+    r = np.random.default_rng(5)
+    pool = fo.KVPool(cfg)
+    states, prompts, at = [], [], 0
+    for L in lens:
+        npg = (L + 3 * B) // cfg.page_size                        # room for two more blocks
+        states.append(fo.new_seq_state(cfg, L, list(range(at, at + npg))))
+        at += npg
+        prompts.append(list(r.integers(1, cfg.vocab, L)))
+    fo.prefill(cfg, W, pool, states, prompts)
+    generated = [[], []]
+    for block in range(2):
+        steps = 0
+        while any(any(st.masked) for st in states):
+            assert fo.finalize_blocks(cfg, W, pool, states) == [False, False]     # nothing to finalize yet
+            fo.focus_step(cfg, W, pool, states)
+            steps += 1
+            assert steps <= B
+        toks = [list(st.tokens) for st in states]
+        stats = [(st.token_sum, st.total_steps) for st in states]
+        assert fo.finalize_blocks(cfg, W, pool, states) == [True, True]
+        for i, st in enumerate(states):
+            generated[i] += toks[i]
+            assert st.prefix_len == lens[i] + (block + 1) * B and all(st.masked) and not any(st.processed)
+            assert (st.token_sum, st.total_steps) == stats[i] and st.token_sum == (block + 1) * B
+    # the cache now equals a fresh prefill of prompt + generated tokens (and the torch dense reference)
+    for i, st in enumerate(states):
+        full = prompts[i] + generated[i]
+        pool2 = fo.KVPool(cfg)
+        st2 = fo.new_seq_state(cfg, len(full), list(range(100, 100 + len(st.pages))))
+        fo.prefill(cfg, W, pool2, [st2], [full])
+        _, kvs = dense_reference(cfg, W, full[:-B], full[-B:])
+        for l in range(cfg.n_layers):
+            K1, V1 = pool.read(l, st.pages, list(range(len(full))))
+            K2, V2 = pool2.read(l, st2.pages, list(range(len(full))))
+            np.testing.assert_allclose(K1, K2, rtol=1e-9, atol=1e-10)
+            np.testing.assert_allclose(V1, V2, rtol=1e-9, atol=1e-10)
+            np.testing.assert_allclose(K1, kvs[l][0], rtol=1e-9, atol=1e-10)
+            np.testing.assert_allclose(V1, kvs[l][1], rtol=1e-9, atol=1e-10)
+
+
+def test_finalize_needs_room_and_a_complete_block():
+    cfg = tiny_cfg(n_layers=2, keep_ratio=1.0)
+    W = tiny_weights(cfg, seed=22)
+    pool, states, _ = tiny_batch(cfg, W, [8], seed=3)            # pages for exactly one block
+    for _ in range(cfg.block_size):
+        fo.focus_step(cfg, W, pool, states)
+    assert not any(states[0].masked)
+    assert fo.finalize_blocks(cfg, W, pool, states) == [False] and states[0].prefix_len == 8
