@@ -152,6 +152,7 @@ class Workload:
     conf_threshold: float = 0.9
     steps: int = 1
     shuffle_pages: bool = False
+    extra_blocks: int = 0       # further blocks each sequence will generate (pages and positions are planned for them)
 
     @property
     def torch_dtype(self):
@@ -165,7 +166,7 @@ class Workload:
         return uniform_ints(self.seed, TID_PREFIX_LEN, self.batch, self.prefix_lo, self.prefix_hi)
 
     def pages_per_seq(self, prefix_len: int) -> int:
-        return (prefix_len + self.block_size + self.page_size - 1) // self.page_size
+        return (prefix_len + self.block_size * (1 + self.extra_blocks) + self.page_size - 1) // self.page_size
 
     def page_tables(self, prefix_lens: Optional[List[int]] = None):
         """(tables, n_pages): consecutive logical page ids per sequence, optionally mapped

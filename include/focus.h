@@ -131,7 +131,8 @@ int focus_init(const focus_config *cfg, const focus_weights *weights, void *kv_p
  * running statistics are reset too unless keep_stats != 0, App. E.3.1 "state persistence").
  *   seq_slot      host [n_seq] slot of each sequence, or NULL for 0..n_seq-1
  *   prefix_len    host [n_seq]
- *   page_table    host [n_seq, table_stride]: physical pages covering prefix_len + B tokens
+ *   page_table    host [n_seq, table_stride]: physical pages covering at least prefix_len + B tokens; further
+ *                 entries up to the first negative one are pages for the blocks generated later
  *   prompt_tokens host, the prompts concatenated in order (sum of prefix_len ids), or NULL.
  *                 Not NULL: computes the exact prefix K/V of every layer (the prompt is cut into blocks of
  *                 B tokens, each attends to all earlier blocks and bidirectionally to itself; Sec. 2).
@@ -166,6 +167,16 @@ int focus_select_compact(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const 
  *                        residual stream leaving layer_end - 1 */
 int focus_run_layers(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32_t *seq_slot, const uint64_t *keep_bits,
                      const uint64_t *vis_bits, int32_t layer_begin, int32_t layer_end, float *hidden);
+
+/* Multi-block generation (the loop around Alg. 1; App. E.3.1 "state persistence and reset").  Every listed
+ * sequence whose block has no masked position left gets one last forward of the whole block with its committed
+ * tokens through all layers, so that the K/V it leaves behind is the exact K/V of those tokens; then the block
+ * becomes prefix (prefix_len += B) and a new all-masked block starts; the running statistics persist.  Sequences
+ * that still have masked positions are untouched, and so are sequences without room: the new prefix must not exceed
+ * max_prefix_len and the page list given to focus_prefill_kv must cover prefix_len + 2 B tokens.
+ *   finalized     device [n_seq] out: 1 where the block was finalized, else 0; or NULL
+ * Enqueues only (no host synchronisation). */
+int focus_finalize_blocks(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32_t *seq_slot, int32_t *finalized);
 
 /* Stage entry: confidence-based commit (Alg. 1 Decode_and_Verify, App. E.3.1 statistics) on caller-given
  * confidences.  Updates the slot state and writes out->tokens, mask_bits, n_decoded.

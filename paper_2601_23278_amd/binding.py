@@ -71,6 +71,7 @@ def load_library() -> C.CDLL:
         "focus_select_compact": [P, P, I, P, P, P, C.POINTER(focus_step_out)],
         "focus_commit": [P, P, I, P, P, P, P, P, C.POINTER(focus_step_out)],
         "focus_run_layers": [P, P, I, P, P, P, I, I, P],
+        "focus_finalize_blocks": [P, P, I, P, P],
         "focus_get_state": [P, I, C.POINTER(focus_seq_state)],
         "focus_set_state": [P, I, C.POINTER(focus_seq_state)],
         "focus_set_timing": [P, I],
@@ -86,7 +87,7 @@ def load_library() -> C.CDLL:
 
 _lib = load_library()
 EXPORTS = ["focus_workspace_bytes", "focus_kv_pool_bytes", "focus_init", "focus_prefill_kv", "focus_step",
-           "focus_select_compact", "focus_commit", "focus_run_layers", "focus_get_state", "focus_set_state", "focus_set_timing",
+           "focus_select_compact", "focus_commit", "focus_run_layers", "focus_finalize_blocks", "focus_get_state", "focus_set_state", "focus_set_timing",
            "focus_get_kernel_time", "focus_free", "focus_last_error"]
 
 
@@ -152,7 +153,7 @@ class Focus:
                          seq_slot: Optional[Sequence[int]] = None, keep_stats: bool = False, stream=None):
         n = len(prefix_len)
         stride = max([len(t) for t in page_table] + [1])
-        flat = [0] * (n * stride)
+        flat = [-1] * (n * stride)
         for b, t in enumerate(page_table):
             flat[b * stride:b * stride + len(t)] = list(t)
         prompts = None if prompt_tokens is None else [t for row in prompt_tokens for t in row]
@@ -179,6 +180,10 @@ class Focus:
                          layer_end: int, hidden: torch.Tensor, seq_slot: Optional[torch.Tensor] = None, stream=None):
         _check(_lib.focus_run_layers(self._ctx, self._stream(stream), n_seq, _ptr(seq_slot), _ptr(keep_bits), _ptr(vis_bits),
                                      layer_begin, layer_end, _ptr(hidden)), self._ctx)
+
+    def focus_finalize_blocks(self, n_seq: int, finalized: Optional[torch.Tensor] = None, seq_slot: Optional[torch.Tensor] = None,
+                              stream=None):
+        _check(_lib.focus_finalize_blocks(self._ctx, self._stream(stream), n_seq, _ptr(seq_slot), _ptr(finalized)), self._ctx)
 
     def focus_get_state(self, slot: int) -> focus_seq_state:
         st = focus_seq_state()

@@ -5,6 +5,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <algorithm>
 #include <new>
 
 #include "focus_internal.h"
@@ -17,7 +18,7 @@ constexpr int kMaxTimed = 4096;
 constexpr int kTargetAttnGroups = 2048;   // (sequence, kv head, split) workgroups the attention launch aims for
 
 struct Plan {
-  size_t off_prefix_len, off_page_table, off_tokens, off_mask, off_processed, off_token_sum, off_total_steps;
+  size_t off_prefix_len, off_page_count, off_page_table, off_tokens, off_mask, off_processed, off_token_sum, off_total_steps;
   size_t off_rope, off_resid, off_resid_p, off_normed, off_qkv, off_q_p, off_attn, off_gate_up, off_act, off_logits;
   size_t off_partial, off_delta, off_K, off_keep, off_n_keep, off_vis, off_cu, off_cu_full, off_row_map,
       off_row_map_full, off_total, off_total_full, off_conf, off_argmax, off_prompt, off_prompt_off, off_prompt_len,
@@ -38,6 +39,7 @@ Plan make_plan(const focus_config &c) {
   p.max_rows = (int)rows;
   p.max_pos = c.max_prefix_len + c.block_size;
   p.off_prefix_len = take(nb * 4);
+  p.off_page_count = take(nb * 4);
   p.off_page_table = take(nb * p.table_stride * 4);
   p.off_tokens = take(rows * 4);
   p.off_mask = take(nb * 8);
@@ -124,7 +126,8 @@ struct focus_ctx {
   fk::SlotState slots() const {
     return {at<int32_t>(plan.off_prefix_len), at<int32_t>(plan.off_page_table), plan.table_stride,
             at<int32_t>(plan.off_tokens), at<uint64_t>(plan.off_mask), at<uint64_t>(plan.off_processed),
-            at<int64_t>(plan.off_token_sum), at<int32_t>(plan.off_total_steps), cfg.max_batch};
+            at<int64_t>(plan.off_token_sum), at<int32_t>(plan.off_total_steps), cfg.max_batch,
+            at<int32_t>(plan.off_page_count), cfg.max_prefix_len};
   }
   fk::KvLayer kv_layer(int l) const {
     size_t layer_bytes = (size_t)cfg.n_pages * 2 * cfg.n_kv_heads * cfg.page_size * cfg.head_dim * esize(cfg.dtype);
@@ -409,7 +412,7 @@ int focus_prefill_kv(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int3
   const int B = g.block_size;
   // host-side checks: slots distinct and in range, lengths in range, pages in range and enough of them
   std::vector<char> used(g.max_batch, 0);
-  std::vector<int32_t> slots(n_seq), table((size_t)n_seq * pl.table_stride, 0), offs(n_seq);
+  std::vector<int32_t> slots(n_seq), table((size_t)n_seq * pl.table_stride, 0), offs(n_seq), counts(n_seq);
   long long total_prompt = 0;
   int max_len = 0;
   for (int b = 0; b < n_seq; ++b) {
@@ -421,11 +424,15 @@ int focus_prefill_kv(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int3
     if (L < 0 || L > g.max_prefix_len) return fail(ctx, FOCUS_EINVAL, "sequence %d: prefix_len %d outside 0..%d", b, L, g.max_prefix_len);
     int need = (L + B + g.page_size - 1) / g.page_size;
     if (need > table_stride) return fail(ctx, FOCUS_EINVAL, "sequence %d: needs %d pages, table_stride is %d", b, need, table_stride);
-    for (int i = 0; i < need; ++i) {
+    int have = 0;                              // leading valid entries; a negative entry ends the list
+    for (int i = 0; i < table_stride && i < pl.table_stride; ++i) {
       int pg = page_table[(size_t)b * table_stride + i];
+      if (pg < 0 && i >= need) break;
       if (pg < 0 || pg >= g.n_pages) return fail(ctx, FOCUS_EINVAL, "sequence %d: page %d outside 0..%d", b, pg, g.n_pages - 1);
       table[(size_t)b * pl.table_stride + i] = pg;
+      have = i + 1;
     }
+    counts[b] = have;
     offs[b] = (int32_t)total_prompt;
     total_prompt += L;
     max_len = L > max_len ? L : max_len;
@@ -441,6 +448,8 @@ int focus_prefill_kv(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int3
   for (int b = 0; b < n_seq; ++b)
     HIP_TRY(ctx, hipMemcpyAsync(st.page_table + (size_t)slots[b] * pl.table_stride, table.data() + (size_t)b * pl.table_stride,
                                 (size_t)pl.table_stride * 4, hipMemcpyHostToDevice, s));
+  for (int b = 0; b < n_seq; ++b)
+    HIP_TRY(ctx, hipMemcpyAsync(st.page_count + slots[b], &counts[b], 4, hipMemcpyHostToDevice, s));
   int32_t *d_len = ctx->at<int32_t>(pl.off_prompt_len), *d_off = ctx->at<int32_t>(pl.off_prompt_off);
   int32_t *d_slots = ctx->at<int32_t>(pl.off_slot_list);
   HIP_TRY(ctx, hipMemcpyAsync(d_len, prefix_len, (size_t)n_seq * 4, hipMemcpyHostToDevice, s));
@@ -608,6 +617,33 @@ int focus_run_layers(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int3
     layer_rest(ctx, s, l, packed, resid_p, ctx->at<char>(pl.off_qkv), qkv_w, vis_bits);
   }
   HIP_TRY(ctx, hipMemcpyAsync(hidden, resid_p, (size_t)cap * g.hidden * 4, hipMemcpyDeviceToDevice, s));
+  HIP_TRY(ctx, hipGetLastError());
+  return FOCUS_OK;
+}
+
+int focus_finalize_blocks(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32_t *seq_slot, int32_t *finalized) {
+  if (int rc = check_batch(ctx, n_seq)) return rc;
+  if (n_seq == 0) return FOCUS_OK;
+  const focus_config &g = ctx->cfg;
+  const Plan &pl = ctx->plan;
+  hipStream_t s = (hipStream_t)hip_stream;
+  const int B = g.block_size;
+  const int qkv_w = (g.n_q_heads + 2 * g.n_kv_heads) * g.head_dim;
+  fk::SlotState st = ctx->slots();
+  uint64_t *keep = ctx->at<uint64_t>(pl.off_keep);
+  int32_t *cu = ctx->at<int32_t>(pl.off_cu), *row_map = ctx->at<int32_t>(pl.off_row_map), *total = ctx->at<int32_t>(pl.off_total);
+  float *resid = ctx->at<float>(pl.off_resid_p);
+  // the prefixes may grow by one block: keep the host-side bound the attention launch is sized with
+  ctx->max_total = std::min(ctx->max_total + B, g.max_prefix_len + B);
+  fk::finalize_pick(s, n_seq, B, g.page_size, seq_slot, st, keep, finalized);
+  fk::scan_compact(s, n_seq, B, keep, cu, row_map, total);
+  RowSet rs{{n_seq * B, total}, {row_map, seq_slot, B}, n_seq, cu, B, nullptr};
+  fk::embed(s, g.dtype, ctx->embed, g.hidden, rs.rows, rs.ri, st, g.mask_token_id, resid);
+  for (int l = 0; l < g.n_layers; ++l) {
+    layer_qkv(ctx, s, l, rs, resid);
+    layer_rest(ctx, s, l, rs, resid, ctx->at<char>(pl.off_qkv), qkv_w, keep);
+  }
+  fk::finalize_advance(s, n_seq, B, seq_slot, st, keep, g.mask_token_id);
   HIP_TRY(ctx, hipGetLastError());
   return FOCUS_OK;
 }

@@ -31,6 +31,8 @@ struct SlotState {
   int64_t *token_sum;
   int32_t *total_steps;
   int32_t max_batch;
+  int32_t *page_count;    // pages each slot's table really holds
+  int32_t max_prefix_len;
 };
 
 // Slot of batch entry b.  A caller-supplied slot list lives in device memory and cannot be checked on the
@@ -137,6 +139,11 @@ void prefill_chunk_setup(hipStream_t s, int n_seq, int B, int chunk, const int32
                          uint64_t *keep_bits);
 void reset_block_state(hipStream_t s, int n_seq, int B, const int32_t *seq_slot, SlotState st,
                        const int32_t *prefix_len, int mask_id, int keep_stats);
+// Multi-block generation: picks the sequences whose block is complete (and that have room for another block),
+// and, after their last forward, turns the block into prefix and starts a new all-masked block.
+void finalize_pick(hipStream_t s, int n_seq, int B, int page_size, const int32_t *seq_slot, SlotState st, uint64_t *keep_bits,
+                   int32_t *finalized);
+void finalize_advance(hipStream_t s, int n_seq, int B, const int32_t *seq_slot, SlotState st, const uint64_t *keep_bits, int mask_id);
 void fill_u64(hipStream_t s, uint64_t *p, int n, uint64_t v);
 void iota_rows(hipStream_t s, int32_t *row_map, int32_t *cu, int n_seq, int B, int32_t *total);
 // order[rank] = batch entry, ranked by descending prefix length (ties: lower entry first)

@@ -313,6 +313,36 @@ void reset_block_state(hipStream_t s, int n_seq, int B, const int32_t *seq_slot,
   if (n_seq > 0) k_reset_block<<<n_seq, 64, 0, s>>>(n_seq, B, seq_slot, st, prefix_len, mask_id, keep_stats);
 }
 
+__global__ void k_finalize_pick(int n_seq, int B, int P, const int32_t *seq_slot, SlotState st, uint64_t *keep_bits, int32_t *finalized) {
+  const int b = blockIdx.x * 64 + threadIdx.x;
+  if (b >= n_seq) return;
+  const int slot = slot_of(seq_slot, b, st);
+  const uint64_t all = B >= 64 ? ~0ull : ((1ull << B) - 1);
+  const int L = st.prefix_len[slot];
+  const bool done = (st.mask_bits[slot] & all) == 0 && L + B <= st.max_prefix_len && (long)L + 2 * B <= (long)st.page_count[slot] * P;
+  keep_bits[b] = done ? all : 0;
+  if (finalized) finalized[b] = done ? 1 : 0;
+}
+void finalize_pick(hipStream_t s, int n_seq, int B, int page_size, const int32_t *seq_slot, SlotState st, uint64_t *keep_bits,
+                   int32_t *finalized) {
+  if (n_seq > 0) k_finalize_pick<<<(n_seq + 63) / 64, 64, 0, s>>>(n_seq, B, page_size, seq_slot, st, keep_bits, finalized);
+}
+
+__global__ void k_finalize_advance(int n_seq, int B, const int32_t *seq_slot, SlotState st, const uint64_t *keep_bits, int mask_id) {
+  const int b = blockIdx.x;
+  if (keep_bits[b] == 0) return;
+  const int slot = slot_of(seq_slot, b, st);
+  if ((int)threadIdx.x < B) st.tokens[slot * B + threadIdx.x] = mask_id;
+  if (threadIdx.x == 0) {
+    st.prefix_len[slot] += B;
+    st.mask_bits[slot] = B >= 64 ? ~0ull : ((1ull << B) - 1);
+    st.processed_bits[slot] = 0;
+  }
+}
+void finalize_advance(hipStream_t s, int n_seq, int B, const int32_t *seq_slot, SlotState st, const uint64_t *keep_bits, int mask_id) {
+  if (n_seq > 0) k_finalize_advance<<<n_seq, 64, 0, s>>>(n_seq, B, seq_slot, st, keep_bits, mask_id);
+}
+
 // Prefill: chunk c of each prompt becomes the (fully unmasked) block at prefix_len = c * B; sequences whose
 // prompt has ended contribute no rows.
 __global__ void k_prefill_chunk(int n_seq, int B, int chunk, const int32_t *seq_slot, SlotState st, const int32_t *prompt,

@@ -58,7 +58,7 @@ def open_session(wl: Workload, device="cuda:0", seq_ids: Optional[Sequence[int]]
     ids = list(range(wl.batch)) if seq_ids is None else list(seq_ids)
     lens = [lens_all[b] for b in ids]
     tables = [tables_all[b] for b in ids]
-    cfg = config_from_workload(wl, max_batch=len(ids), max_prefix_len=max(lens), n_pages=n_pages)
+    cfg = config_from_workload(wl, max_batch=len(ids), max_prefix_len=max(lens) + wl.extra_blocks * wl.block_size, n_pages=n_pages)
     for k, v in cfg_over.items():
         setattr(cfg, k, v)
     dev = torch.device(device)

@@ -352,3 +352,71 @@ def test_step_argument_errors():
     with pytest.raises(pk.FocusError):
         sess.focus.focus_prefill_kv([8], [[999]])          # page outside the pool
     sess.focus.focus_free()
+
+
+def test_multi_block_generation_with_finalize_fp32():
+    """Two blocks generated back to back: steps until a block has no masked position, focus_finalize_blocks, next
+    block.  Tokens, masks, counters and prefix lengths must equal the oracle's at every step; at the end the whole
+    cache (prompt + both generated blocks, every layer) must equal the oracle's."""
+    pk, runner = _pk()
+    wl = fi.workload("c1_tiny", keep_ratio=0.5, extra_blocks=2)
+    cfg, W, pool, states, lens, tables, n_pages = oracle_batch(wl)
+    sess = runner.open_session(wl, DEV)
+    n, B = wl.batch, wl.block_size
+    outs = Outs(pk, wl, n)
+    fin = torch.zeros(n, dtype=torch.int32, device=DEV)
+    for block in range(2):
+        for step in range(B + 1):
+            sess.focus.focus_finalize_blocks(n, fin)
+            done_gpu = fin.cpu().tolist()
+            done_ora = fo.finalize_blocks(cfg, W, pool, states)
+            assert [bool(x) for x in done_gpu] == done_ora, (block, step)
+            if all(done_ora):
+                break
+            assert not any(done_ora)                             # equal commit counts: the sequences finish together
+            sess.focus.focus_step(n, out=outs.struct)
+            g = outs.host()
+            tr = fo.focus_step(cfg, W, pool, states, score_cast=lambda d: d.astype(np.float32).astype(np.float64),
+                               conf_cast=lambda c: c.astype(np.float32).astype(np.float64))
+            T = tr.cu[-1]
+            assert [positions_of(u64(k), B) for k in g["keep_bits"]] == tr.keep
+            assert row_relerr(g["logits"][:T], tr.logits) <= 1e-3
+            for b, st in enumerate(states):
+                assert [int(t) for t in g["tokens"][b]] == st.tokens
+                assert u64(g["mask_bits"][b]) == bits_of([p for p in range(B) if st.masked[p]])
+        else:
+            raise AssertionError("block did not finish")
+        for b, st in enumerate(states):
+            s = sess.focus.focus_get_state(b)
+            assert (s.prefix_len, s.token_sum, s.total_steps, s.processed_bits) == (lens[b] + (block + 1) * B, st.token_sum, st.total_steps, 0)
+            assert s.mask_bits == (1 << B) - 1 and st.prefix_len == s.prefix_len
+    kv = sess.kv_pool.cpu().numpy()
+    P = wl.page_size
+    for l in range(wl.n_layers):
+        for b, st in enumerate(states):
+            for t in range(st.prefix_len):
+                pg = pool.layers[l][st.pages[t // P]]
+                page = kv[l, st.pages[t // P]]
+                got_k = page[0][:, t % P, :]
+                got_v = page[1].reshape(wl.n_kv_heads, wl.head_dim, P)[:, :, t % P]
+                assert relerr(got_k, pg[0, :, t % P, :]) <= 1e-3 and relerr(got_v, pg[1, :, t % P, :]) <= 1e-3, (l, b, t)
+    # no room for a third block beyond the planned two extra ones is needed here; a sequence without room is left alone
+    sess.focus.focus_free()
+
+
+def test_finalize_skips_incomplete_blocks_and_sequences_without_room():
+    pk, runner = _pk()
+    wl = fi.workload("c1_tiny", keep_ratio=1.0)                  # pages for the current block only
+    sess = runner.open_session(wl, DEV)
+    n, B = wl.batch, wl.block_size
+    fin = torch.ones(n, dtype=torch.int32, device=DEV)
+    sess.focus.focus_finalize_blocks(n, fin)
+    assert fin.cpu().tolist() == [0] * n                         # all masked: nothing to finalize
+    for _ in range(B):
+        sess.focus.focus_step(n)
+    assert all(sess.focus.focus_get_state(b).mask_bits == 0 for b in range(n))
+    before = [sess.focus.focus_get_state(b).prefix_len for b in range(n)]
+    sess.focus.focus_finalize_blocks(n, fin)
+    assert fin.cpu().tolist() == [0] * n                         # complete, but no pages / positions planned for another block
+    assert [sess.focus.focus_get_state(b).prefix_len for b in range(n)] == before
+    sess.focus.focus_free()
