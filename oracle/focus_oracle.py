@@ -70,6 +70,7 @@ class OracleConfig:
     constraints: int = 0          # bit0 AR-context preservation, bit1 placeholder integrity
     conf_threshold: float = 0.9
     placeholder_unprocessed_only: bool = False   # alternative reading of placeholder integrity
+    intra_block_cache: int = 0    # 1: delayed intra-block K/V cache with the neighbour-aware stability criterion (Sec. 4.3)
 
 
 @dataclass
@@ -80,13 +81,14 @@ class SeqState:
     tokens: List[int]                      # committed id per block position (meaningless where masked)
     masked: List[bool]                     # M: position still holds the mask token
     processed: List[bool]                  # P: position has K/V in the layers above the eviction layer
+    cached: Optional[List[bool]] = None    # C: position's K/V is frozen in every layer (Sec. 4.3); None = none
     token_sum: int = 0                     # running sum of tokens decoded per step
     total_steps: int = 0                   # number of steps this sequence took part in
 
 
 def new_seq_state(cfg: OracleConfig, prefix_len: int, pages: Sequence[int]) -> SeqState:
     B = cfg.block_size
-    return SeqState(prefix_len, list(pages), [cfg.mask_token_id] * B, [True] * B, [False] * B)
+    return SeqState(prefix_len, list(pages), [cfg.mask_token_id] * B, [True] * B, [False] * B, [False] * B)
 
 
 class Weights:
@@ -196,8 +198,9 @@ def importance(q: np.ndarray, k: np.ndarray, maxpool_k: int = 3) -> np.ndarray:
     the block; the softmax normalises over the B block keys only (so each row contributes one
     unit of mass and the deltas are zero-sum, as Sec. 4.1 says of them); pooling runs along the
     key index on the pre-softmax scores, stride 1, same length."""
-    B, Hq, D = q.shape
-    g = Hq // k.shape[1]
+    Hq, D = q.shape[1], q.shape[2]
+    B = k.shape[0]                      # keys: every block position; queries: the rows that are forwarded (all B unless
+    g = Hq // k.shape[1]                # some positions are cached, Sec. 4.3)
     I = np.zeros(B)
     for h in range(Hq):
         S = q[:, h, :] @ k[:, h // g, :].T / math.sqrt(D)          # [i, j]
@@ -254,7 +257,7 @@ def budget(cfg: OracleConfig, dI: Sequence[float], masked: Sequence[bool], token
 # Alg. 1 phase 3: selection
 
 def select(cfg: OracleConfig, dI: Sequence[float], masked: Sequence[bool], processed: Sequence[bool],
-           K: int) -> List[int]:
+           K: int, cached: Optional[Sequence[bool]] = None) -> List[int]:
     """The retained set S of one sequence, ascending.
 
     K >= B keeps the whole block (no eviction: the step is the dense block decode).  Otherwise the
@@ -263,11 +266,16 @@ def select(cfg: OracleConfig, dI: Sequence[float], masked: Sequence[bool], proce
     masked j below max(S) (bit1).  The predecessor of position 0 lies in the prefix; predecessors are
     added once, for the top-K picks only."""
     B = cfg.block_size
+    cached = [False] * B if cached is None else cached
+    uncached = [j for j in range(B) if not cached[j]]
+    # with the intra-block cache, decoded tokens that are not frozen yet stay in: they are owed the forward with
+    # their final token in every layer (Sec. 4.3 "decoded and forwarded one additional time")
+    owed = [j for j in uncached if not masked[j]] if cfg.intra_block_cache else []
     if K >= B:
-        return list(range(B))
+        return uncached
     cand = [j for j in range(B) if masked[j]]
     if K <= 0 or not cand:
-        return []
+        return owed
 
     def key(j):
         v = float(dI[j])
@@ -275,13 +283,13 @@ def select(cfg: OracleConfig, dI: Sequence[float], masked: Sequence[bool], proce
     top = sorted(cand, key=key)[:min(K, len(cand))]
     S = set(top)
     if cfg.constraints & 1:
-        S |= {i - 1 for i in top if i >= 1}
+        S |= {i - 1 for i in top if i >= 1 and not cached[i - 1]}
     if cfg.constraints & 2:
         mx = max(S)
         for j in range(mx):
             if masked[j] and (not cfg.placeholder_unprocessed_only or not processed[j]):
                 S.add(j)
-    return sorted(S)
+    return sorted(S | set(owed))
 
 
 def compact(keep: Sequence[Sequence[int]], B: int):
@@ -373,6 +381,7 @@ class StepTrace:
     delta_I: List[np.ndarray] = field(default_factory=list)
     K: List[int] = field(default_factory=list)
     keep: List[List[int]] = field(default_factory=list)
+    uncached: List[List[int]] = field(default_factory=list)  # per sequence, the positions forwarded through layers <= e
     cu: List[int] = field(default_factory=list)
     row_map: List[int] = field(default_factory=list)
     hidden_full: Optional[np.ndarray] = None                   # [n*B, h] residual stream entering layer e
@@ -412,37 +421,49 @@ def focus_step(cfg: OracleConfig, W: Weights, pool: KVPool, seqs: List[SeqState]
     if e >= cfg.n_layers:
         raise ValueError("eviction layer outside the model")
 
+    # rows of the layers up to e: the positions whose K/V is not frozen (all B without the intra-block cache)
+    for st in seqs:
+        if st.cached is None:
+            st.cached = [False] * B
+    U = [[p for p in range(B) if not st.cached[p]] for st in seqs]
+    tr.uncached = U
+    cuU = [0]
+    for u in U:
+        cuU.append(cuU[-1] + len(u))
     # block input: mask embedding where masked, committed token's embedding elsewhere
-    ids = [[cfg.mask_token_id if st.masked[p] else st.tokens[p] for p in range(B)] for st in seqs]
-    X = np.concatenate([W.embed[np.array(row)] for row in ids], axis=0) if n else np.zeros((0, cfg.hidden))
-    all_pos = list(range(B))
+    ids = [[cfg.mask_token_id if st.masked[p] else st.tokens[p] for p in U[b]] for b, st in enumerate(seqs)]
+    X = np.concatenate([W.embed[np.array(row, dtype=np.int64)].reshape(len(row), cfg.hidden) for row in ids], axis=0) \
+        if n else np.zeros((0, cfg.hidden))
+    abs_pos = np.array([st.prefix_len + p for b, st in enumerate(seqs) for p in U[b]], dtype=np.int64)
 
-    # layers 0 .. e-1 on the whole block
+    def block_keys(l, st):
+        Kc, _ = pool.read(l, st.pages, [st.prefix_len + p for p in range(B)])
+        return Kc
+
+    # layers 0 .. e-1 on those rows; they see the prefix and all B in-block keys (frozen ones from the cache)
     for l in range(e):
         w = W.layer(l)
-        abs_pos = np.concatenate([st.prefix_len + np.arange(B) for st in seqs])
         q, k, v = _project_qkv(cfg, w, X, abs_pos)
         attn = np.empty_like(q)
         for b, st in enumerate(seqs):
-            sl = slice(b * B, (b + 1) * B)
-            for p in range(B):
-                pool.write(l, st.pages, st.prefix_len + p, k[b * B + p], v[b * B + p])
+            sl = slice(cuU[b], cuU[b + 1])
+            for i, p in enumerate(U[b]):
+                pool.write(l, st.pages, st.prefix_len + p, k[sl.start + i], v[sl.start + i])
             if l == e - 1 and cfg.importance_mode == 0:
-                tr.I_prev.append(importance(q[sl], k[sl], cfg.maxpool_k))
+                tr.I_prev.append(importance(q[sl], block_keys(l, st), cfg.maxpool_k))
             Kc, Vc = pool.read(l, st.pages, list(range(st.prefix_len + B)))
             attn[sl] = _attention(cfg, q[sl], Kc, Vc)
         X = _finish_layer(cfg, w, X, attn)
     tr.hidden_full = X.copy()
 
-    # layer e: projections and K/V fill for the whole block, importance, delta
+    # layer e: projections and K/V fill for those rows, importance, delta
     w = W.layer(e)
-    abs_pos = np.concatenate([st.prefix_len + np.arange(B) for st in seqs]) if n else np.zeros(0)
     q, k, v = _project_qkv(cfg, w, X, abs_pos)
     for b, st in enumerate(seqs):
-        sl = slice(b * B, (b + 1) * B)
-        for p in range(B):
-            pool.write(e, st.pages, st.prefix_len + p, k[b * B + p], v[b * B + p])
-        Ie = importance(q[sl], k[sl], cfg.maxpool_k)
+        sl = slice(cuU[b], cuU[b + 1])
+        for i, p in enumerate(U[b]):
+            pool.write(e, st.pages, st.prefix_len + p, k[sl.start + i], v[sl.start + i])
+        Ie = importance(q[sl], block_keys(e, st), cfg.maxpool_k)
         tr.I_evict.append(Ie)
         d = Ie - tr.I_prev[b] if cfg.importance_mode == 0 else Ie.copy()
         tr.delta_I.append(score_cast(d) if score_cast is not None else d)
@@ -456,14 +477,14 @@ def focus_step(cfg: OracleConfig, W: Weights, pool: KVPool, seqs: List[SeqState]
             K = budget(cfg, tr.delta_I[b], st.masked, st.token_sum, st.total_steps,
                        None if k_override is None else k_override[b])
             tr.K.append(K)
-            S = select(cfg, tr.delta_I[b], st.masked, st.processed, K)
+            S = select(cfg, tr.delta_I[b], st.masked, st.processed, K, st.cached)
         tr.keep.append(S)
         for p in S:
             st.processed[p] = True
     tr.cu, tr.row_map = compact(tr.keep, B)
-    rows = np.array(tr.row_map, dtype=np.int64)
+    rows = np.array([cuU[b] + U[b].index(p) for b in range(n) for p in tr.keep[b]], dtype=np.int64)
 
-    # gather; rest of layer e on the retained rows (they see all B fresh keys of layer e)
+    # gather; rest of layer e on the retained rows (they see all B keys of layer e)
     Xp, qp = X[rows], q[rows]
     attn = np.empty_like(qp)
     for b, st in enumerate(seqs):
@@ -501,9 +522,16 @@ def focus_step(cfg: OracleConfig, W: Weights, pool: KVPool, seqs: List[SeqState]
     tr.argmax = am
     for b, st in enumerate(seqs):
         sl = slice(tr.cu[b], tr.cu[b + 1])
+        unmasked_before = [not m for m in st.masked]
         D = commit(cfg, st, tr.keep[b], tr.conf[sl], am[sl])
         tr.committed.append(D)
         tr.n_decoded.append(len(D))
+        if cfg.intra_block_cache:
+            # neighbour-aware stability (Sec. 4.3, App. E.3.1): a position is frozen once it and its right neighbour
+            # were both decoded before this step, i.e. both went through this forward with their final tokens
+            for p in tr.keep[b]:
+                if unmasked_before[p] and (p == B - 1 or unmasked_before[p + 1]):
+                    st.cached[p] = True
     return tr
 
 
@@ -545,18 +573,20 @@ def finalize_blocks(cfg: OracleConfig, W: Weights, pool: KVPool, seqs: List[SeqS
         if any(st.masked) or not room:
             done.append(False)
             continue
-        X = W.embed[np.array(st.tokens)]
-        pos = st.prefix_len + np.arange(B)
+        rows_p = [p for p in range(B) if not (st.cached and st.cached[p])]      # frozen positions keep their K/V
+        X = W.embed[np.array([st.tokens[p] for p in rows_p], dtype=np.int64)].reshape(len(rows_p), cfg.hidden)
+        pos = st.prefix_len + np.array(rows_p, dtype=np.int64)
         for l in range(cfg.n_layers):
             w = W.layer(l)
             q, k, v = _project_qkv(cfg, w, X, pos)
-            for p in range(B):
-                pool.write(l, st.pages, st.prefix_len + p, k[p], v[p])
+            for i, p in enumerate(rows_p):
+                pool.write(l, st.pages, st.prefix_len + p, k[i], v[i])
             Kc, Vc = pool.read(l, st.pages, list(range(st.prefix_len + B)))
             X = _finish_layer(cfg, w, X, _attention(cfg, q, Kc, Vc))
         st.prefix_len += B
         st.tokens = [cfg.mask_token_id] * B
         st.masked = [True] * B
         st.processed = [False] * B
+        st.cached = [False] * B
         done.append(True)
     return done

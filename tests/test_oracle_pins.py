@@ -597,3 +597,123 @@ def test_finalize_needs_room_and_a_complete_block():
         fo.focus_step(cfg, W, pool, states)
     assert not any(states[0].masked)
     assert fo.finalize_blocks(cfg, W, pool, states) == [False] and states[0].prefix_len == 8
+
+
+# ---------------------------------------------------------------------------------------------
+# intra-block K/V cache with the neighbour-aware stability criterion (Sec. 4.3, App. E.3.1)
+
+def snapshot_block_kv(cfg, pool, st):
+    toks = [st.prefix_len + p for p in range(cfg.block_size)]
+    return [tuple(a.copy() for a in pool.read(l, st.pages, toks)) for l in range(cfg.n_layers)]
+
+
+def reference_step_rows(cfg, W, prefix_kv, block_kv_before, st_before, U, S, processed_after):
+    """Independent (torch) statement of one step for one sequence, given as INPUTS the prefix K/V and the block's K/V
+    before the step: rows U go through layers <= e, rows S through the rest; a row's keys are the prefix, the fresh
+    K/V of the rows of its layer, and the given (old) K/V of every other visible block position.  Returns the logits
+    of the rows S."""
+    B, e, D, Hq, Hkv = cfg.block_size, cfg.evict_layer, cfg.head_dim, cfg.n_q_heads, cfg.n_kv_heads
+    L = st_before["prefix_len"]
+    ids = [cfg.mask_token_id if st_before["masked"][p] else st_before["tokens"][p] for p in U]
+    X = torch.from_numpy(W.embed)[torch.tensor(ids)]
+    inv = cfg.rope_base ** (-torch.arange(0, D, 2, dtype=torch.float64) / D)
+
+    def rot(x, pos):
+        ang = torch.tensor(pos, dtype=torch.float64)[:, None] * inv[None]
+        c, s = torch.cos(ang)[:, None, :], torch.sin(ang)[:, None, :]
+        a, b = x[..., :D // 2], x[..., D // 2:]
+        return torch.cat([a * c - b * s, b * c + a * s], -1)
+    rows = list(U)
+    for l in range(cfg.n_layers):
+        w = {k: torch.from_numpy(np.asarray(v)) for k, v in W.layer(l).items()}
+        if l > e and rows is not S:
+            X = X[[rows.index(p) for p in S]]
+            rows = list(S)
+        u = F.rms_norm(X, (cfg.hidden,), w["attn_norm"], eps=cfg.rms_eps)
+        q, k, v = F.linear(u, w["w_qkv"]).split([Hq * D, Hkv * D, Hkv * D], dim=-1)
+        pos = [L + p for p in rows]
+        q, k, v = rot(q.view(-1, Hq, D), pos), rot(k.view(-1, Hkv, D), pos), v.view(-1, Hkv, D)
+        if l == e:                                    # layer e: projections for U, attention only for S
+            keep_idx = [rows.index(p) for p in S]
+        visible = list(range(B)) if l <= e else [p for p in range(B) if processed_after[p]]
+        Kb = torch.from_numpy(block_kv_before[l][0]).clone()
+        Vb = torch.from_numpy(block_kv_before[l][1]).clone()
+        for i, p in enumerate(rows):
+            Kb[p], Vb[p] = k[i], v[i]
+        Kall = torch.cat([torch.from_numpy(prefix_kv[l][0]), Kb[visible]])
+        Vall = torch.cat([torch.from_numpy(prefix_kv[l][1]), Vb[visible]])
+        if l == e:
+            X, q, rows = X[keep_idx], q[keep_idx], list(S)
+        o = F.scaled_dot_product_attention(q.transpose(0, 1)[None], Kall.transpose(0, 1)[None], Vall.transpose(0, 1)[None],
+                                           enable_gqa=True)[0].transpose(0, 1).reshape(len(rows), Hq * D)
+        X = X + F.linear(o, w["w_o"])
+        u = F.rms_norm(X, (cfg.hidden,), w["mlp_norm"], eps=cfg.rms_eps)
+        g, up = F.linear(u, w["w_gate_up"]).split([cfg.ffn, cfg.ffn], dim=-1)
+        X = X + F.linear(F.silu(g) * up, w["w_down"])
+    return F.linear(F.rms_norm(X, (cfg.hidden,), torch.from_numpy(W.final_norm), eps=cfg.rms_eps), torch.from_numpy(W.lm_head)).numpy()
+
+
+def test_intra_block_cache_rows_freezing_and_reference():
+    cfg = tiny_cfg(n_layers=3, keep_ratio=0.25, conf_threshold=0.05, intra_block_cache=1)    # low threshold: several commits per step
+    W = tiny_weights(cfg, seed=31, scale=0.6)
+    B = cfg.block_size
+    pool, states, _ = tiny_batch(cfg, W, [12], seed=11)
+    st = states[0]
+    frozen = {}
+    saw_cached_step = False
+    for step in range(2 * B):
+        if not any(st.masked):
+            break
+        before = dict(prefix_len=st.prefix_len, masked=list(st.masked), tokens=list(st.tokens), cached=list(st.cached))
+        prefix_kv = [pool.read(l, st.pages, list(range(st.prefix_len))) for l in range(cfg.n_layers)]
+        block_kv = snapshot_block_kv(cfg, pool, st)
+        tr = fo.focus_step(cfg, W, pool, states)
+        U, S = tr.uncached[0], tr.keep[0]
+        # rows: exactly the positions that were not frozen; decoded-but-not-frozen positions are always retained
+        assert U == [p for p in range(B) if not before["cached"][p]]
+        assert set(S) <= set(U) and {p for p in U if not before["masked"][p]} <= set(S)
+        assert abs(tr.I_evict[0].sum() - len(U) * cfg.n_q_heads) < 1e-9
+        # neighbour-aware rule, written out
+        unm = [not m for m in before["masked"]]
+        expect = [before["cached"][p] or (p in S and unm[p] and (p == B - 1 or unm[p + 1])) for p in range(B)]
+        assert st.cached == expect
+        # frozen K/V never changes again
+        after = snapshot_block_kv(cfg, pool, st)
+        for p, kv in frozen.items():
+            for l in range(cfg.n_layers):
+                assert np.array_equal(after[l][0][p], kv[l][0]) and np.array_equal(after[l][1][p], kv[l][1])
+        for p in range(B):
+            if st.cached[p] and p not in frozen:
+                frozen[p] = [(after[l][0][p].copy(), after[l][1][p].copy()) for l in range(cfg.n_layers)]
+        # the step's logits against the independent statement (the K/V before the step are inputs)
+        if S:
+            ref = reference_step_rows(cfg, W, prefix_kv, block_kv, before, U, S, st.processed)
+            np.testing.assert_allclose(tr.logits, ref, rtol=1e-9, atol=1e-10)
+        saw_cached_step = saw_cached_step or len(U) < B
+    assert saw_cached_step and frozen, "the scenario must reach steps with frozen positions"
+    assert not any(st.masked)
+    # finalisation forwards only what is not frozen, then clears the state
+    block_kv = snapshot_block_kv(cfg, pool, st)
+    was_cached = list(st.cached)
+    st.pages = st.pages + [900, 901]                              # room for another block
+    L0 = st.prefix_len
+    assert fo.finalize_blocks(cfg, W, pool, states) == [True]
+    toks = [L0 + p for p in range(B)]
+    for l in range(cfg.n_layers):
+        Kc, Vc = pool.read(l, st.pages, toks)
+        for p in range(B):
+            if was_cached[p]:
+                assert np.array_equal(Kc[p], block_kv[l][0][p]) and np.array_equal(Vc[p], block_kv[l][1][p])
+    assert st.cached == [False] * B and st.prefix_len == L0 + B
+
+
+def test_intra_block_cache_off_or_idle_changes_nothing():
+    # with nothing decoded before a step the cache cannot freeze anything: first steps equal the plain method
+    for ratio in (0.25, 1.0):
+        outs = []
+        for flag in (0, 1):
+            cfg = tiny_cfg(n_layers=3, keep_ratio=ratio, intra_block_cache=flag)
+            W = tiny_weights(cfg, seed=32)
+            pool, states, _ = tiny_batch(cfg, W, [8, 12], seed=12)
+            outs.append(fo.focus_step(cfg, W, pool, states))
+        assert outs[0].keep == outs[1].keep and np.array_equal(outs[0].logits, outs[1].logits)
