@@ -6,6 +6,8 @@
 //                does not take.
 //   k_gemm_mfma  bf16 on the matrix cores (see below).
 // M is read from device memory when the row count is only known on the device (packed batch after eviction).
+#include <algorithm>
+
 #include "focus_internal.h"
 
 namespace fk {
@@ -222,19 +224,28 @@ static void launch_mfma(hipStream_t s, const void *A, const void *W, int N, int 
 }
 
 // ---------------------------------------------------------------------------------------------
-// Large problems: 256x256x64 tiles, 8 wavefronts (2 x 4, each 128 x 64), K-slabs loaded straight into LDS
+// Large problems: BM x 256 x 64 tiles (BM = 256 or 128), 8 wavefronts (2 x 4), K-slabs loaded straight into LDS
 // (global_load_lds_dwordx4: lane l of an instruction fills the 16-byte slot l of a 1 KB block = 8 tile rows, so
-// the bank swizzle is applied by choosing which chunk a lane fetches), two LDS stages: slab k + 1 streams in
-// while slab k is multiplied, one barrier per slab.  A quarter fewer bytes per flop through the vector memory
-// path than 256x128, which is what bounds these GEMMs; it needs >= 3 tiles per CU to pay off.
+// the bank swizzle is applied by choosing which chunk a lane fetches), two LDS stages, software-pipelined by hand:
+//   * the fragments of k-step s + 1 are read from LDS while the MFMAs of step s run (two register sets);
+//   * one barrier per slab, placed before the last k-step: by then every wavefront has read all of the current slab
+//     and the next one has landed, so the loads of the slab after the next start right behind the barrier;
+//   * loads are spread between the MFMAs (a burst of 8 direct-to-LDS loads per wavefront stalls the matrix pipe for
+//     longer than the loads take on their own: measured 37 % of the MFMA rate against 100 % when interleaved).
+// The waits for the loads are explicit: the compiler does not order LDS reads behind direct-to-LDS loads.
 #define FK_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 #define FK_GLB_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
 
-template <int EPI>
-__global__ __launch_bounds__(512, 2) void k_gemm_mfma_big(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W, int N, int K,
-                                                          Rows rows, void *out, int ldo, int tiles_m, int tiles_n) {
-  constexpr int BM = 256, BN = 256, BK = 64, WM = 128, WN = 64, TM = 4, TN = 2, IA = 4, IB = 4, STAGE = (BM + BN) * 128;
-  extern __shared__ __attribute__((aligned(1024))) unsigned char lds_big[];
+template <int BM, int EPI>
+__global__ __launch_bounds__(512, 2) void k_gemm_pipe(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W, int N, int K,
+                                                      Rows rows, void *out, int ldo, int tiles_m, int tiles_n) {
+  constexpr int BN = 256, BK = 64, WM = BM / 2, WN = 64, TM = WM / 32, TN = 2, IA = BM / 64, IB = 4, NI = IA + IB;
+  constexpr int STAGE = (BM + BN) * 128, NMF = TM * TN;
+  // loads issued in the k-step right behind the barrier; the rest follow in the first k-step of the next slab
+  constexpr int L0 = NI / 2, L1 = NI - L0;
+  static_assert(L0 <= NMF && L1 <= NMF && TM + TN <= NMF, "one load and one fragment read per MFMA at most");
+  extern __shared__ __attribute__((aligned(1024))) unsigned char lds_pipe[];
+  unsigned char *const lds = lds_pipe;
   const int M = rows.count ? min(*rows.count, rows.cap) : rows.cap;
   const int total = tiles_m * tiles_n;
   const int per_xcd = (total + 7) / 8;
@@ -245,29 +256,26 @@ __global__ __launch_bounds__(512, 2) void k_gemm_mfma_big(const bf16_t *__restri
   const int gsz = min(tiles_m - first_m, GROUP);
   const int m0 = (first_m + in_group % gsz) * BM, n0 = (in_group / gsz) * (EPI == EPI_SILU_MUL ? BN / 2 : BN);
   if (m0 >= M) return;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = (wave >> 2) * WM, wn = (wave & 3) * WN;
-  // per-lane source of each load instruction: instruction q of this wavefront covers tile rows (wave * 4 + q) * 8 .. + 7
-  const bf16_t *ga[IA], *gb[IB];
+  // per-lane byte offsets of this wavefront's load instructions: instruction q covers tile rows (wave * I + q) * 8 .. + 7
+  unsigned voa[IA], vob[IB];
 #pragma unroll
   for (int q = 0; q < IA; ++q) {
     const int r = (wave * IA + q) * 8 + (lane >> 3), c = (lane & 7) ^ ((r >> 1) & 7);
-    ga[q] = A + (size_t)min(m0 + r, M - 1) * K + c * 8;
+    voa[q] = (unsigned)min(m0 + r, M - 1) * (unsigned)K * 2u + c * 16;
   }
 #pragma unroll
   for (int q = 0; q < IB; ++q) {
     const int r = (wave * IB + q) * 8 + (lane >> 3), c = (lane & 7) ^ ((r >> 1) & 7);
     const int wrow = EPI == EPI_SILU_MUL ? ((r >> 5) & 1) * (N / 2) + n0 + (r / WN) * 32 + (r & 31) : n0 + r;   // see k_gemm_mfma
-    gb[q] = W + (size_t)min(wrow, N - 1) * K + c * 8;
+    vob[q] = (unsigned)min(wrow, N - 1) * (unsigned)K * 2u + c * 16;
   }
-  auto issue = [&](int kt, int buf) {
-    unsigned char *sA = lds_big + buf * STAGE, *sB = sA + BM * 128;
-#pragma unroll
-    for (int q = 0; q < IA; ++q)
-      __builtin_amdgcn_global_load_lds(FK_GLB_PTR(ga[q] + (size_t)kt * BK), FK_LDS_PTR(sA + (wave * IA + q) * 1024), 16, 0, 0);
-#pragma unroll
-    for (int q = 0; q < IB; ++q)
-      __builtin_amdgcn_global_load_lds(FK_GLB_PTR(gb[q] + (size_t)kt * BK), FK_LDS_PTR(sB + (wave * IB + q) * 1024), 16, 0, 0);
+  const unsigned char *Ab = (const unsigned char *)A, *Wb = (const unsigned char *)W;
+  auto gl = [&](int i, int kt, int buf) {     // load instruction i (A: 0 .. IA-1, W: IA .. NI-1) of slab kt into stage buf
+    const unsigned char *src = (i < IA ? Ab : Wb) + (size_t)kt * (BK * 2);
+    unsigned char *dst = lds + buf * STAGE + (i < IA ? (wave * IA + i) * 1024 : BM * 128 + (wave * IB + (i - IA)) * 1024);
+    __builtin_amdgcn_global_load_lds(FK_GLB_PTR(src + (i < IA ? voa[i < IA ? i : 0] : vob[i < IA ? 0 : i - IA])), FK_LDS_PTR(dst), 16, 0, 0);
   };
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -277,34 +285,52 @@ __global__ __launch_bounds__(512, 2) void k_gemm_mfma_big(const bf16_t *__restri
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
   const int frow = lane & 31, fch = lane >> 5;
+  unsigned ra[TM], rb[TN], swa[TM], swb[TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) { const int r = wm + i * 32 + frow; ra[i] = r * 128; swa[i] = (r >> 1) & 7; }
+#pragma unroll
+  for (int j = 0; j < TN; ++j) { const int r = wn + j * 32 + frow; rb[j] = BM * 128 + r * 128; swb[j] = (r >> 1) & 7; }
+  bf16x8 fa[2][TM], fb[2][TN];
+  auto rd = [&](int f, int ks, int buf, int slot) {   // fragment f (A: 0 .. TM-1, W: TM .. TM+TN-1) of k-step ks
+    if (f < TM) fa[slot][f < TM ? f : 0] = *(const bf16x8 *)(lds + buf * STAGE + ra[f < TM ? f : 0] + (((2 * ks + fch) ^ swa[f < TM ? f : 0]) << 4));
+    else fb[slot][f < TM ? 0 : f - TM] = *(const bf16x8 *)(lds + buf * STAGE + rb[f < TM ? 0 : f - TM] + (((2 * ks + fch) ^ swb[f < TM ? 0 : f - TM]) << 4));
+  };
   const int nk = K / BK;
-  issue(0, 0);
-  __builtin_amdgcn_s_waitcnt(0);
+#pragma unroll
+  for (int i = 0; i < NI; ++i) gl(i, 0, 0);
+#pragma unroll
+  for (int i = 0; i < L0; ++i) gl(i, min(1, nk - 1), 1);
+  __builtin_amdgcn_s_waitcnt(0x0F70 | L0);   // vmcnt(L0): slab 0 has landed
   __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    if (kt + 1 < nk) issue(kt + 1, (kt + 1) & 1);
-    const unsigned char *As = lds_big + (kt & 1) * STAGE, *Bs = As + BM * 128;
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 af[TM], bfr[TN];
-#pragma unroll
-      for (int i = 0; i < TM; ++i) {
-        const int r = wm + i * 32 + frow;
-        af[i] = *(const bf16x8 *)(As + r * 128 + (((2 * ks + fch) ^ ((r >> 1) & 7)) << 4));
-      }
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        const int r = wn + j * 32 + frow;
-        bfr[j] = *(const bf16x8 *)(Bs + r * 128 + (((2 * ks + fch) ^ ((r >> 1) & 7)) << 4));
-      }
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-    }
-    __builtin_amdgcn_s_waitcnt(0);       // the next slab has landed (this wavefront's part) ...
-    __syncthreads();                     // ... and everyone's, and everyone is done reading the current one
+  for (int f = 0; f < TM + TN; ++f) rd(f, 0, 0, 0);
+
+  // one k-step: the MFMAs on register set `cur`; behind MFMA s, fragment read s of the next k-step, and (when nl > 0)
+  // a load on every NMF / nl-th MFMA
+#define FK_STEP(cur, next_ks, next_buf, nl, lfirst, lslab, lbuf)                                        \
+  {                                                                                                     \
+    _Pragma("unroll") for (int s = 0; s < NMF; ++s) {                                                   \
+      const int i = s / TN, j = s % TN;                                                                 \
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][i], fb[cur][j], acc[i][j], 0, 0, 0);  \
+      if (s < TM + TN) rd(s, next_ks, next_buf, (cur) ^ 1);                                             \
+      if ((nl) > 0 && s % (NMF / ((nl) > 0 ? (nl) : 1)) == NMF / ((nl) > 0 ? (nl) : 1) - 1 && s / (NMF / ((nl) > 0 ? (nl) : 1)) < (nl)) \
+        gl((lfirst) + s / (NMF / ((nl) > 0 ? (nl) : 1)), lslab, lbuf);                                  \
+      __builtin_amdgcn_sched_barrier(0);                                                                \
+    }                                                                                                   \
   }
+  for (int kt = 0; kt < nk; ++kt) {
+    const int buf = kt & 1;
+    // beyond the last slab the loads repeat it (into a stage nobody reads any more): the loop body has no branches
+    const int s1 = min(kt + 1, nk - 1), s2 = min(kt + 2, nk - 1);
+    FK_STEP(0, 1, buf, L1, L0, s1, buf ^ 1)
+    FK_STEP(1, 2, buf, 0, 0, s1, buf ^ 1)
+    FK_STEP(0, 3, buf, 0, 0, s1, buf ^ 1)
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wavefront's part of slab kt + 1 has landed
+    __syncthreads();                      // ... and everyone's; everyone has read all of slab kt
+    FK_STEP(1, 0, buf ^ 1, L0, 0, s2, buf)
+  }
+#undef FK_STEP
+  __builtin_amdgcn_s_waitcnt(0x0F70);
   if (EPI == EPI_SILU_MUL) {
     const int gn = n0 + (wn / WN) * 32 + (lane & 31);
 #pragma unroll
@@ -330,27 +356,28 @@ __global__ __launch_bounds__(512, 2) void k_gemm_mfma_big(const bf16_t *__restri
     }
 }
 
-template <int EPI>
-static bool launch_big_epi(hipStream_t s, const bf16_t *a, const bf16_t *w, int N, int K, Rows rows, void *out, int ldo, int tiles_m, int tiles_n) {
-  constexpr int kLds = 2 * 512 * 128;
-  static bool ready = false;             // the 128 KB of dynamic LDS have to be allowed once per kernel
+template <int BM, int EPI>
+static bool launch_pipe_epi(hipStream_t s, const bf16_t *a, const bf16_t *w, int N, int K, Rows rows, void *out, int ldo, int tiles_m, int tiles_n) {
+  constexpr int kLds = 2 * (BM + 256) * 128;
+  static bool ready = false;             // the dynamic LDS size has to be allowed once per kernel
   if (!ready) {
-    if (hipFuncSetAttribute((const void *)k_gemm_mfma_big<EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, kLds) != hipSuccess) return false;
+    if (hipFuncSetAttribute((const void *)k_gemm_pipe<BM, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, kLds) != hipSuccess) return false;
     ready = true;
   }
   const int grid = ((tiles_m * tiles_n + 7) / 8) * 8;
-  k_gemm_mfma_big<EPI><<<grid, 512, kLds, s>>>(a, w, N, K, rows, out, ldo, tiles_m, tiles_n);
+  k_gemm_pipe<BM, EPI><<<grid, 512, kLds, s>>>(a, w, N, K, rows, out, ldo, tiles_m, tiles_n);
   return true;
 }
 
-static bool launch_big(hipStream_t s, const void *A, const void *W, int N, int K, Rows rows, int epi, void *out, int ldo) {
-  const int tiles_m = (rows.cap + 255) / 256;
+template <int BM>
+static bool launch_pipe(hipStream_t s, const void *A, const void *W, int N, int K, Rows rows, int epi, void *out, int ldo) {
+  const int tiles_m = (rows.cap + BM - 1) / BM;
   const int tiles_n = epi == EPI_SILU_MUL ? (N / 2 + 127) / 128 : (N + 255) / 256;
   const bf16_t *a = (const bf16_t *)A, *w = (const bf16_t *)W;
-  if (epi == EPI_SILU_MUL) return launch_big_epi<EPI_SILU_MUL>(s, a, w, N, K, rows, out, ldo, tiles_m, tiles_n);
-  if (epi == EPI_STORE) return launch_big_epi<EPI_STORE>(s, a, w, N, K, rows, out, ldo, tiles_m, tiles_n);
-  if (epi == EPI_ADD_F32) return launch_big_epi<EPI_ADD_F32>(s, a, w, N, K, rows, out, ldo, tiles_m, tiles_n);
-  return launch_big_epi<EPI_STORE_F32>(s, a, w, N, K, rows, out, ldo, tiles_m, tiles_n);
+  if (epi == EPI_SILU_MUL) return launch_pipe_epi<BM, EPI_SILU_MUL>(s, a, w, N, K, rows, out, ldo, tiles_m, tiles_n);
+  if (epi == EPI_STORE) return launch_pipe_epi<BM, EPI_STORE>(s, a, w, N, K, rows, out, ldo, tiles_m, tiles_n);
+  if (epi == EPI_ADD_F32) return launch_pipe_epi<BM, EPI_ADD_F32>(s, a, w, N, K, rows, out, ldo, tiles_m, tiles_n);
+  return launch_pipe_epi<BM, EPI_STORE_F32>(s, a, w, N, K, rows, out, ldo, tiles_m, tiles_n);
 }
 
 bool gemm_fuses_silu_mul(int dtype, const void *A, const void *W, int N, int K) {
@@ -363,12 +390,14 @@ void gemm(hipStream_t s, int dtype, const void *A, const void *W, int N, int K, 
   if (dtype == FOCUS_F32) { launch_valu<float>(s, A, W, N, K, rows, epilogue, out, ldo); return; }
   const bool aligned = K % 64 == 0 && ((uintptr_t)A & 15) == 0 && ((uintptr_t)W & 15) == 0;
   if (!aligned) { launch_valu<bf16_t>(s, A, W, N, K, rows, epilogue, out, ldo); return; }
-  // 256x256 direct-to-LDS tiles for tall or very wide problems (measured: +15 % at 8192 rows and on the
-  // vocabulary projection, no gain at 2048 rows x 24576), else
-  // 256x128 tiles when they still give every CU two workgroups, 128x128 tiles below that
-  const long n_cols = epilogue == EPI_SILU_MUL ? N / 2 : N;
-  const long tiles_256 = (long)((rows.cap + 255) / 256) * ((n_cols + (epilogue == EPI_SILU_MUL ? 127 : 255)) / (epilogue == EPI_SILU_MUL ? 128 : 256));
-  if (tiles_256 >= 768 && (rows.cap >= 4096 || tiles_256 >= 2048) && launch_big(s, A, W, N, K, rows, epilogue, out, ldo)) return;
+  // tile choice: the pipelined kernels run one workgroup per CU; take the largest tile that still gives every CU work
+  // (a byte offset of a row must fit 32 bits there), else the register-staged kernel with smaller tiles
+  const long n_tiles = epilogue == EPI_SILU_MUL ? (N / 2 + 127) / 128 : (N + 255) / 256;
+  const bool fits32 = (double)std::max(rows.cap, N) * K * 2 < 4.0e9;
+  const long t256 = (long)((rows.cap + 255) / 256) * n_tiles, t128 = (long)((rows.cap + 127) / 128) * n_tiles;
+  const int choice = t256 >= 160 ? 256 : (t128 >= 160 ? 128 : 0);
+  if (fits32 && choice == 256 && launch_pipe<256>(s, A, W, N, K, rows, epilogue, out, ldo)) return;
+  if (fits32 && choice == 128 && launch_pipe<128>(s, A, W, N, K, rows, epilogue, out, ldo)) return;
   const long tiles_big = (long)((rows.cap + 255) / 256) * ((N + 127) / 128);
   if (tiles_big >= 512) launch_mfma<256, 128>(s, A, W, N, K, rows, epilogue, out, ldo);
   else launch_mfma<128, 128>(s, A, W, N, K, rows, epilogue, out, ldo);
