@@ -225,22 +225,28 @@ static void launch_mfma(hipStream_t s, const void *A, const void *W, int N, int 
 
 // ---------------------------------------------------------------------------------------------
 // Large problems: BM x 256 x 64 tiles (BM = 256 or 128), 8 wavefronts (2 x 4), K-slabs loaded straight into LDS
-// (global_load_lds_dwordx4: lane l of an instruction fills the 16-byte slot l of a 1 KB block = 8 tile rows, so
-// the bank swizzle is applied by choosing which chunk a lane fetches), two LDS stages, software-pipelined by hand:
+// (buffer_load_dwordx4 ... lds: lane l of an instruction fills the 16-byte slot l of a 1 KB block = 8 tile rows, so
+// the bank swizzle is applied by choosing which chunk a lane fetches; rows beyond the matrix fall outside the buffer
+// descriptor and read as zero), two LDS stages, software-pipelined by hand:
 //   * the fragments of k-step s + 1 are read from LDS while the MFMAs of step s run (two register sets);
 //   * one barrier per slab, placed before the last k-step: by then every wavefront has read all of the current slab
 //     and the next one has landed, so the loads of the slab after the next start right behind the barrier;
 //   * loads are spread between the MFMAs (a burst of 8 direct-to-LDS loads per wavefront stalls the matrix pipe for
-//     longer than the loads take on their own: measured 37 % of the MFMA rate against 100 % when interleaved).
+//     longer than the loads take on their own: measured 37 % of the MFMA rate against 100 % when interleaved);
+//   * the loop handles two slabs per trip, so the stage is a compile-time constant, LDS addresses are loop-invariant
+//     registers plus immediates, and the loads take their slab offset from a scalar register: no vector ALU work
+//     competes with the MFMAs for issue slots.
 // The waits for the loads are explicit: the compiler does not order LDS reads behind direct-to-LDS loads.
+// LDS layout: A stage 0, A stage 1, W stage 0, W stage 1 (so that both stages of an operand are within the 16-bit
+// immediate offset of one base register).
 #define FK_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
-#define FK_GLB_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
 
 template <int BM, int EPI>
 __global__ __launch_bounds__(512, 2) void k_gemm_pipe(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W, int N, int K,
                                                       Rows rows, void *out, int ldo, int tiles_m, int tiles_n) {
+#if defined(__HIP_DEVICE_COMPILE__)   // buffer-resource builtins exist in the device pass only
   constexpr int BN = 256, BK = 64, WM = BM / 2, WN = 64, TM = WM / 32, TN = 2, IA = BM / 64, IB = 4, NI = IA + IB;
-  constexpr int STAGE = (BM + BN) * 128, NMF = TM * TN;
+  constexpr int ASTAGE = BM * 128, WSTAGE = BN * 128, WBASE = 2 * ASTAGE, NMF = TM * TN;
   // loads issued in the k-step right behind the barrier; the rest follow in the first k-step of the next slab
   constexpr int L0 = NI / 2, L1 = NI - L0;
   static_assert(L0 <= NMF && L1 <= NMF && TM + TN <= NMF, "one load and one fragment read per MFMA at most");
@@ -258,24 +264,28 @@ __global__ __launch_bounds__(512, 2) void k_gemm_pipe(const bf16_t *__restrict__
   if (m0 >= M) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = (wave >> 2) * WM, wn = (wave & 3) * WN;
+  // raw buffers over the valid rows: an offset at or beyond the size reads zero without touching memory
+  __amdgpu_buffer_rsrc_t rs_a = __builtin_amdgcn_make_buffer_rsrc((void *)A, 0, (unsigned)M * (unsigned)K * 2u, 0x00020000);
+  __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc((void *)W, 0, (unsigned)N * (unsigned)K * 2u, 0x00020000);
   // per-lane byte offsets of this wavefront's load instructions: instruction q covers tile rows (wave * I + q) * 8 .. + 7
   unsigned voa[IA], vob[IB];
 #pragma unroll
   for (int q = 0; q < IA; ++q) {
     const int r = (wave * IA + q) * 8 + (lane >> 3), c = (lane & 7) ^ ((r >> 1) & 7);
-    voa[q] = (unsigned)min(m0 + r, M - 1) * (unsigned)K * 2u + c * 16;
+    voa[q] = (unsigned)(m0 + r) * (unsigned)K * 2u + c * 16;
   }
 #pragma unroll
   for (int q = 0; q < IB; ++q) {
     const int r = (wave * IB + q) * 8 + (lane >> 3), c = (lane & 7) ^ ((r >> 1) & 7);
     const int wrow = EPI == EPI_SILU_MUL ? ((r >> 5) & 1) * (N / 2) + n0 + (r / WN) * 32 + (r & 31) : n0 + r;   // see k_gemm_mfma
-    vob[q] = (unsigned)min(wrow, N - 1) * (unsigned)K * 2u + c * 16;
+    vob[q] = (unsigned)wrow * (unsigned)K * 2u + c * 16;
   }
-  const unsigned char *Ab = (const unsigned char *)A, *Wb = (const unsigned char *)W;
-  auto gl = [&](int i, int kt, int buf) {     // load instruction i (A: 0 .. IA-1, W: IA .. NI-1) of slab kt into stage buf
-    const unsigned char *src = (i < IA ? Ab : Wb) + (size_t)kt * (BK * 2);
-    unsigned char *dst = lds + buf * STAGE + (i < IA ? (wave * IA + i) * 1024 : BM * 128 + (wave * IB + (i - IA)) * 1024);
-    __builtin_amdgcn_global_load_lds(FK_GLB_PTR(src + (i < IA ? voa[i < IA ? i : 0] : vob[i < IA ? 0 : i - IA])), FK_LDS_PTR(dst), 16, 0, 0);
+  auto gl = [&](int i, int soff, int buf) {   // load instruction i (A: 0 .. IA-1, W: IA .. NI-1) of the slab at byte offset soff
+    if (i < IA)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_a, FK_LDS_PTR(lds + buf * ASTAGE + (wave * IA + (i < IA ? i : 0)) * 1024), 16, voa[i < IA ? i : 0], soff, 0, 0);
+    else
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, FK_LDS_PTR(lds + WBASE + buf * WSTAGE + (wave * IB + (i < IA ? 0 : i - IA)) * 1024), 16,
+                                               vob[i < IA ? 0 : i - IA], soff, 0, 0);
   };
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -284,51 +294,61 @@ __global__ __launch_bounds__(512, 2) void k_gemm_pipe(const bf16_t *__restrict__
     for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-  const int frow = lane & 31, fch = lane >> 5;
-  unsigned ra[TM], rb[TN], swa[TM], swb[TN];
+  // fragment addresses: row = base + (lane & 31), logical chunk 2 * ks + (lane >> 5), swizzled with the row (all 32-row
+  // tiles start at a multiple of 32, so the swizzle depends on the lane only)
+  const int frow = lane & 31, fch = lane >> 5, sw = (frow >> 1) & 7;
+  const unsigned char *pa[4], *pb[4];
 #pragma unroll
-  for (int i = 0; i < TM; ++i) { const int r = wm + i * 32 + frow; ra[i] = r * 128; swa[i] = (r >> 1) & 7; }
-#pragma unroll
-  for (int j = 0; j < TN; ++j) { const int r = wn + j * 32 + frow; rb[j] = BM * 128 + r * 128; swb[j] = (r >> 1) & 7; }
+  for (int ks = 0; ks < 4; ++ks) {
+    pa[ks] = lds + (wm + frow) * 128 + (((2 * ks + fch) ^ sw) << 4);
+    pb[ks] = lds + WBASE + (wn + frow) * 128 + (((2 * ks + fch) ^ sw) << 4);
+  }
   bf16x8 fa[2][TM], fb[2][TN];
-  auto rd = [&](int f, int ks, int buf, int slot) {   // fragment f (A: 0 .. TM-1, W: TM .. TM+TN-1) of k-step ks
-    if (f < TM) fa[slot][f < TM ? f : 0] = *(const bf16x8 *)(lds + buf * STAGE + ra[f < TM ? f : 0] + (((2 * ks + fch) ^ swa[f < TM ? f : 0]) << 4));
-    else fb[slot][f < TM ? 0 : f - TM] = *(const bf16x8 *)(lds + buf * STAGE + rb[f < TM ? 0 : f - TM] + (((2 * ks + fch) ^ swb[f < TM ? 0 : f - TM]) << 4));
+  auto rd = [&](int s, int ks, int buf, int slot) {   // s-th fragment read of a k-step, in the order the MFMAs need them
+    const int f = s == 0 ? TM : (s == 1 ? 0 : (s == 2 ? TM + 1 : s - 2));   // W0, A0, W1, A1, A2, ...
+    if (f < TM) fa[slot][f < TM ? f : 0] = *(const bf16x8 *)(pa[ks] + buf * ASTAGE + (f < TM ? f : 0) * 4096);
+    else fb[slot][f < TM ? 0 : f - TM] = *(const bf16x8 *)(pb[ks] + buf * WSTAGE + (f < TM ? 0 : f - TM) * 4096);
   };
-  const int nk = K / BK;
+  const int nk = K / BK, last = (nk - 1) * (BK * 2);   // nk is even (checked by the host)
 #pragma unroll
   for (int i = 0; i < NI; ++i) gl(i, 0, 0);
 #pragma unroll
-  for (int i = 0; i < L0; ++i) gl(i, min(1, nk - 1), 1);
+  for (int i = 0; i < L0; ++i) gl(i, min(BK * 2, last), 1);
   __builtin_amdgcn_s_waitcnt(0x0F70 | L0);   // vmcnt(L0): slab 0 has landed
   __syncthreads();
 #pragma unroll
-  for (int f = 0; f < TM + TN; ++f) rd(f, 0, 0, 0);
+  for (int s = 0; s < TM + TN; ++s) rd(s, 0, 0, 0);
 
   // one k-step: the MFMAs on register set `cur`; behind MFMA s, fragment read s of the next k-step, and (when nl > 0)
   // a load on every NMF / nl-th MFMA
-#define FK_STEP(cur, next_ks, next_buf, nl, lfirst, lslab, lbuf)                                        \
+#define FK_STEP(cur, next_ks, next_buf, nl, lfirst, lsoff, lbuf)                                        \
   {                                                                                                     \
     _Pragma("unroll") for (int s = 0; s < NMF; ++s) {                                                   \
       const int i = s / TN, j = s % TN;                                                                 \
       acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][i], fb[cur][j], acc[i][j], 0, 0, 0);  \
       if (s < TM + TN) rd(s, next_ks, next_buf, (cur) ^ 1);                                             \
       if ((nl) > 0 && s % (NMF / ((nl) > 0 ? (nl) : 1)) == NMF / ((nl) > 0 ? (nl) : 1) - 1 && s / (NMF / ((nl) > 0 ? (nl) : 1)) < (nl)) \
-        gl((lfirst) + s / (NMF / ((nl) > 0 ? (nl) : 1)), lslab, lbuf);                                  \
+        gl((lfirst) + s / (NMF / ((nl) > 0 ? (nl) : 1)), lsoff, lbuf);                                  \
       __builtin_amdgcn_sched_barrier(0);                                                                \
     }                                                                                                   \
   }
-  for (int kt = 0; kt < nk; ++kt) {
-    const int buf = kt & 1;
-    // beyond the last slab the loads repeat it (into a stage nobody reads any more): the loop body has no branches
-    const int s1 = min(kt + 1, nk - 1), s2 = min(kt + 2, nk - 1);
-    FK_STEP(0, 1, buf, L1, L0, s1, buf ^ 1)
-    FK_STEP(1, 2, buf, 0, 0, s1, buf ^ 1)
-    FK_STEP(0, 3, buf, 0, 0, s1, buf ^ 1)
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wavefront's part of slab kt + 1 has landed
-    __syncthreads();                      // ... and everyone's; everyone has read all of slab kt
-    FK_STEP(1, 0, buf ^ 1, L0, 0, s2, buf)
+  // one slab held in stage `buf`; beyond the last slab the loads repeat it (into a stage nobody reads any more), so the
+  // loop body has no branches
+#define FK_SLAB(buf, kt)                                                                                \
+  {                                                                                                     \
+    const int so1 = min(((kt) + 1) * (BK * 2), last), so2 = min(((kt) + 2) * (BK * 2), last);           \
+    FK_STEP(0, 1, buf, L1, L0, so1, (buf) ^ 1)                                                          \
+    FK_STEP(1, 2, buf, 0, 0, so1, (buf) ^ 1)                                                            \
+    FK_STEP(0, 3, buf, 0, 0, so1, (buf) ^ 1)                                                            \
+    __builtin_amdgcn_s_waitcnt(0x0F70); /* vmcnt(0): this wavefront's part of the next slab has landed */ \
+    __syncthreads();                    /* ... and everyone's; everyone has read all of this slab */    \
+    FK_STEP(1, 0, (buf) ^ 1, L0, 0, so2, buf)                                                           \
   }
+  for (int kt = 0; kt < nk; kt += 2) {
+    FK_SLAB(0, kt)
+    FK_SLAB(1, kt + 1)
+  }
+#undef FK_SLAB
 #undef FK_STEP
   __builtin_amdgcn_s_waitcnt(0x0F70);
   if (EPI == EPI_SILU_MUL) {
@@ -354,6 +374,7 @@ __global__ __launch_bounds__(512, 2) void k_gemm_pipe(const bf16_t *__restrict__
         if (gm < M && gn < N) store_out<bf16_t, EPI>(out, (size_t)gm * ldo + gn, acc[i][j][r]);
       }
     }
+#endif
 }
 
 template <int BM, int EPI>
@@ -391,9 +412,9 @@ void gemm(hipStream_t s, int dtype, const void *A, const void *W, int N, int K, 
   const bool aligned = K % 64 == 0 && ((uintptr_t)A & 15) == 0 && ((uintptr_t)W & 15) == 0;
   if (!aligned) { launch_valu<bf16_t>(s, A, W, N, K, rows, epilogue, out, ldo); return; }
   // tile choice: the pipelined kernels run one workgroup per CU; take the largest tile that still gives every CU work
-  // (a byte offset of a row must fit 32 bits there), else the register-staged kernel with smaller tiles
+  // (byte offsets of rows must fit 32 bits there, and the slab count must be even), else the register-staged kernel with smaller tiles
   const long n_tiles = epilogue == EPI_SILU_MUL ? (N / 2 + 127) / 128 : (N + 255) / 256;
-  const bool fits32 = (double)std::max(rows.cap, N) * K * 2 < 4.0e9;
+  const bool fits32 = (double)std::max(rows.cap + 256, N + 256) * K * 2 < 4.0e9 && (K / 64) % 2 == 0;
   const long t256 = (long)((rows.cap + 255) / 256) * n_tiles, t128 = (long)((rows.cap + 127) / 128) * n_tiles;
   const int choice = t256 >= 160 ? 256 : (t128 >= 160 ? 128 : 0);
   if (fits32 && choice == 256 && launch_pipe<256>(s, A, W, N, K, rows, epilogue, out, ldo)) return;
