@@ -210,6 +210,7 @@ void layer_rest(focus_ctx *c, hipStream_t s, int l, const RowSet &rs, float *res
     a.part_o = c->plan.part_entries ? c->at<float>(c->plan.off_part_o) : nullptr;
     a.part_ml = c->plan.part_entries ? c->at<float>(c->plan.off_part_ml) : nullptr;
     a.order = rs.order;
+    a.warm = fk::Warm{c->w_o[l], (size_t)g.hidden * q_w * esize(g.dtype)};
     attention_split(c, rs.n_seq, rs.rows.cap, &a.chunk, &a.launch_splits);
     a.max_splits = a.launch_splits;
     fk::attention(s, a); }
@@ -217,12 +218,16 @@ void layer_rest(focus_ctx *c, hipStream_t s, int l, const RowSet &rs, float *res
   { Timed t(c, s, FOCUS_KC_POINTWISE); fk::rmsnorm(s, g.dtype, resid, c->mlp_norm[l], normed, g.hidden, g.rms_eps, rs.rows); }
   if (fk::gemm_fuses_silu_mul(g.dtype, normed, c->w_gate_up[l], 2 * g.ffn, g.hidden)) {
     Timed t(c, s, FOCUS_KC_GEMM);
-    fk::gemm(s, g.dtype, normed, c->w_gate_up[l], 2 * g.ffn, g.hidden, rs.rows, fk::EPI_SILU_MUL, act, g.ffn);
+    fk::gemm(s, g.dtype, normed, c->w_gate_up[l], 2 * g.ffn, g.hidden, rs.rows, fk::EPI_SILU_MUL, act, g.ffn,
+             fk::Warm{c->w_down[l], (size_t)g.hidden * g.ffn * esize(g.dtype)});
   } else {
     { Timed t(c, s, FOCUS_KC_GEMM); fk::gemm(s, g.dtype, normed, c->w_gate_up[l], 2 * g.ffn, g.hidden, rs.rows, fk::EPI_STORE, gate_up, 2 * g.ffn); }
     { Timed t(c, s, FOCUS_KC_POINTWISE); fk::silu_mul(s, g.dtype, gate_up, act, g.ffn, rs.rows); }
   }
-  { Timed t(c, s, FOCUS_KC_GEMM); fk::gemm(s, g.dtype, act, c->w_down[l], g.hidden, g.ffn, rs.rows, fk::EPI_ADD_F32, resid, g.hidden); }
+  { Timed t(c, s, FOCUS_KC_GEMM);
+    const size_t qkv_bytes = (size_t)(g.n_q_heads + 2 * g.n_kv_heads) * g.head_dim * g.hidden * esize(g.dtype);
+    fk::gemm(s, g.dtype, act, c->w_down[l], g.hidden, g.ffn, rs.rows, fk::EPI_ADD_F32, resid, g.hidden,
+             l + 1 < g.n_layers ? fk::Warm{c->w_qkv[l + 1], qkv_bytes} : fk::Warm()); }
 }
 
 void attention_split(const focus_ctx *c, int n_seq, int rows_cap, int *chunk, int *splits) {

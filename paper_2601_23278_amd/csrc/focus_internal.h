@@ -67,8 +67,28 @@ bool gemm_fuses_silu_mul(int dtype, const void *A, const void *W, int N, int K);
 void embed(hipStream_t s, int dtype, const void *table, int hidden, Rows rows, RowIndex ri, SlotState st,
            int mask_id, float *resid);
 void rmsnorm(hipStream_t s, int dtype, const float *x, const void *w, void *y, int hidden, float eps, Rows rows);
+// Memory the kernel may touch on the side so that the next kernel finds it in the memory-side cache (a hint: kernels
+// that cannot do it ignore it).
+struct Warm {
+  const void *ptr = nullptr;
+  size_t bytes = 0;
+};
 void gemm(hipStream_t s, int dtype, const void *A, const void *W, int N, int K, Rows rows, int epilogue,
-          void *out, int ldo);
+          void *out, int ldo, Warm warm = Warm());
+// Warm-up helper for kernels with one- or two-dimensional grids of short workgroups: the workgroups of the last round
+// (the last min(grid, 256) in launch order) each read one dword of every 128-byte line of their share.  Returns a value
+// the caller must keep alive (e.g. store it under a condition that never holds).
+__device__ __forceinline__ unsigned warm_touch(const void *ptr, size_t bytes, int n_threads) {
+  if (!ptr || !bytes) return 0;
+  const long n_groups = (long)gridDim.x * gridDim.y, id = blockIdx.x + (long)blockIdx.y * gridDim.x;
+  const long shares = n_groups < 256 ? n_groups : 256, share = id - (n_groups - shares);
+  if (share < 0) return 0;
+  const size_t lines = (bytes + 127) / 128, per = (lines + shares - 1) / shares;
+  const size_t l0 = (size_t)share * per, l1 = l0 + per < lines ? l0 + per : lines;
+  unsigned acc = 0;
+  for (size_t l = l0 + threadIdx.x; l < l1; l += n_threads) acc ^= __builtin_nontemporal_load((const unsigned *)((const char *)ptr + l * 128));
+  return acc;
+}
 // Rotates q and k rows of the fused qkv buffer in place and stores k, v of every row into its cache slot.
 void rope_kv_write(hipStream_t s, int dtype, void *qkv, int n_q_heads, Rows rows, RowIndex ri, SlotState st,
                    KvLayer kv, const float2 *rope_table);
@@ -88,6 +108,7 @@ struct AttnArgs {
   float *part_o, *part_ml;       // split-K/V partials: [rows, H_q, max_splits, D] and [.., 2]
   int chunk, max_splits, launch_splits;
   const int32_t *order;          // batch entries sorted by descending prefix length (longest first), or null
+  Warm warm;                     // weights of the projection that follows (bf16 kernel only)
 };
 void attention(hipStream_t s, const AttnArgs &a);
 // Eq. 2 per (sequence, query head) on the full-block qkv buffer: partial[b, h, j].

@@ -256,6 +256,10 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_mfma(AttnArgs a) {
     if (more) issue_v(tile + 1);
   }
 
+  // the last workgroups to start (the shortest sequences), once through their own K/V, pull the next projection's
+  // weights into the memory-side cache: any earlier and the K/V stream would push them out again
+  const unsigned warm_acc = warm_touch(a.warm.ptr, a.warm.bytes, NW * 64);
+  if (warm_acc == 0x9e3779b9u && a.chunk < 0) ((unsigned *)a.out)[0] = warm_acc;   // never true: keeps the loads
   if (!qvalid) return;
   const float l_tot = l + __shfl_xor(l, 32);
   if (nsplit == 1) {

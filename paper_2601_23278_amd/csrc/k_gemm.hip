@@ -241,9 +241,18 @@ static void launch_mfma(hipStream_t s, const void *A, const void *W, int N, int 
 // immediate offset of one base register).
 #define FK_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 
+// Workgroup barrier that orders LDS traffic only: outstanding global loads (which the kernel waits for by count) are
+// not drained, unlike with __syncthreads().
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 template <int BM, int EPI>
 __global__ __launch_bounds__(512, 2) void k_gemm_pipe(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W, int N, int K,
-                                                      Rows rows, void *out, int ldo, int tiles_m, int tiles_n) {
+                                                      Rows rows, void *out, int ldo, int tiles_m, int tiles_n, const void *warm,
+                                                      unsigned warm_bytes) {
 #if defined(__HIP_DEVICE_COMPILE__)   // buffer-resource builtins exist in the device pass only
   constexpr int BN = 256, BK = 64, WM = BM / 2, WN = 64, TM = WM / 32, TN = 2, IA = BM / 64, IB = 4, NI = IA + IB;
   constexpr int ASTAGE = BM * 128, WSTAGE = BN * 128, WBASE = 2 * ASTAGE, NMF = TM * TN;
@@ -280,6 +289,22 @@ __global__ __launch_bounds__(512, 2) void k_gemm_pipe(const bf16_t *__restrict__
     const int wrow = EPI == EPI_SILU_MUL ? ((r >> 5) & 1) * (N / 2) + n0 + (r / WN) * 32 + (r & 31) : n0 + r;   // see k_gemm_mfma
     vob[q] = (unsigned)wrow * (unsigned)K * 2u + c * 16;
   }
+  // Optional: touch `warm_bytes` bytes at `warm` (the weights of the next projection) so that they wait in the memory-side
+  // cache; weights are read once per step and a projection that finds them in HBM runs up to 1.5 times longer.  A
+  // workgroup's share is spread over its slabs: on a "hit" slab each wavefront reads one dword of 64
+  // consecutive 128-byte lines.  The loads go through a descriptor of exactly warm_bytes, so shares beyond the end (and
+  // all of them when there is nothing to warm) are out of range and move no data.  A result is folded into a dummy value
+  // one slab later, when the load has long returned, so nothing waits for it.
+  __amdgpu_buffer_rsrc_t rs_p = __builtin_amdgcn_make_buffer_rsrc((void *)warm, 0, warm_bytes, 0x00020000);
+  // only the workgroups of the last round (one workgroup per CU) take part: what earlier rounds fetch is pushed out of the
+  // cache again by the kernel's own traffic before the next kernel starts
+  const int warm_groups = min((int)gridDim.x, 256), warm_rank = (int)blockIdx.x - ((int)gridDim.x - warm_groups);
+  const unsigned warm_hits = warm_rank < 0 ? 0u : ((warm_bytes + warm_groups - 1) / warm_groups + 65535u) >> 16;   // 64 KB (8 wavefronts x 64 lines) per hit
+  const int warm_stride = warm_hits ? max(1, (K / BK) / (int)warm_hits) : 1;
+  unsigned warm_off = (unsigned)max(warm_rank, 0) * (warm_hits << 16), warm_left = warm_hits;
+  int warm_next = 0;
+  unsigned warm_sink = 0, warm_prev = 0;
+  const unsigned warm_lane = lane * 128 + wave * 8192;
   auto gl = [&](int i, int soff, int buf) {   // load instruction i (A: 0 .. IA-1, W: IA .. NI-1) of the slab at byte offset soff
     if (i < IA)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_a, FK_LDS_PTR(lds + buf * ASTAGE + (wave * IA + (i < IA ? i : 0)) * 1024), 16, voa[i < IA ? i : 0], soff, 0, 0);
@@ -315,7 +340,7 @@ __global__ __launch_bounds__(512, 2) void k_gemm_pipe(const bf16_t *__restrict__
 #pragma unroll
   for (int i = 0; i < L0; ++i) gl(i, min(BK * 2, last), 1);
   __builtin_amdgcn_s_waitcnt(0x0F70 | L0);   // vmcnt(L0): slab 0 has landed
-  __syncthreads();
+  lds_barrier(); 
 #pragma unroll
   for (int s = 0; s < TM + TN; ++s) rd(s, 0, 0, 0);
 
@@ -338,10 +363,17 @@ __global__ __launch_bounds__(512, 2) void k_gemm_pipe(const bf16_t *__restrict__
   {                                                                                                     \
     const int so1 = min(((kt) + 1) * (BK * 2), last), so2 = min(((kt) + 2) * (BK * 2), last);           \
     FK_STEP(0, 1, buf, L1, L0, so1, (buf) ^ 1)                                                          \
+    {                                                                                                   \
+      const bool hit = (kt) == warm_next && warm_left > 0;                                              \
+      const unsigned so = hit ? warm_off : 0x80000000u;                                                 \
+      warm_sink ^= warm_prev;                                                                           \
+      warm_prev = __builtin_amdgcn_raw_buffer_load_b32(rs_p, warm_lane, so, 0);                         \
+      warm_off += hit ? 65536u : 0u; warm_left -= hit ? 1u : 0u; warm_next += hit ? warm_stride : 0;    \
+    }                                                                                                   \
     FK_STEP(1, 2, buf, 0, 0, so1, (buf) ^ 1)                                                            \
     FK_STEP(0, 3, buf, 0, 0, so1, (buf) ^ 1)                                                            \
-    __builtin_amdgcn_s_waitcnt(0x0F70); /* vmcnt(0): this wavefront's part of the next slab has landed */ \
-    __syncthreads();                    /* ... and everyone's; everyone has read all of this slab */    \
+    __builtin_amdgcn_s_waitcnt(0x0F71); /* vmcnt(1): all but the warm-up load: this wavefront's part of the next slab has landed */ \
+    lds_barrier();                     /* ... and everyone's; everyone has read all of this slab */    \
     FK_STEP(1, 0, (buf) ^ 1, L0, 0, so2, buf)                                                           \
   }
   for (int kt = 0; kt < nk; kt += 2) {
@@ -351,34 +383,57 @@ __global__ __launch_bounds__(512, 2) void k_gemm_pipe(const bf16_t *__restrict__
 #undef FK_SLAB
 #undef FK_STEP
   __builtin_amdgcn_s_waitcnt(0x0F70);
+  if ((warm_sink ^ warm_prev) == 0x9e3779b9u && warm_bytes == 1) ((unsigned *)out)[0] = warm_sink;   // keeps the warm-up loads alive; never true
+  // epilogue: accumulator register r of lane l is C[8 * (r / 4) + 4 * (l / 32) + r % 4][l % 32] of its 32x32 tile.
+  // A tile that lies inside the matrix takes the path without per-element bounds checks; there the accumulating
+  // epilogue reads a whole row of 32x32 tiles before it adds and stores (one memory round trip per tile row instead
+  // of one per element).
+  const bool inside = m0 + BM <= M && n0 + (EPI == EPI_SILU_MUL ? BN / 2 : BN) <= (EPI == EPI_SILU_MUL ? N / 2 : N);
+  const int erow = m0 + wm + 4 * (lane >> 5), ecol = lane & 31;
   if (EPI == EPI_SILU_MUL) {
-    const int gn = n0 + (wn / WN) * 32 + (lane & 31);
+    const int gn = n0 + (wn / WN) * 32 + ecol;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int gm = m0 + wm + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        const int gm = erow + i * 32 + 8 * (r >> 2) + (r & 3);
         const float g = acc[i][0][r], u = acc[i][1][r];
-        if (gm < M && gn < N / 2) ((bf16_t *)out)[(size_t)gm * ldo + gn] = (bf16_t)(g / (1.0f + __expf(-g)) * u);
+        if (inside || (gm < M && gn < N / 2)) ((bf16_t *)out)[(size_t)gm * ldo + gn] = (bf16_t)(g / (1.0f + __expf(-g)) * u);
       }
+    return;
+  }
+  if (EPI == EPI_ADD_F32 && inside) {
+    float *o = (float *)out + (size_t)erow * ldo + n0 + wn + ecol;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      float old[TN][16];
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) old[j][r] = o[(size_t)(i * 32 + 8 * (r >> 2) + (r & 3)) * ldo + j * 32];
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[(size_t)(i * 32 + 8 * (r >> 2) + (r & 3)) * ldo + j * 32] = old[j][r] + acc[i][j][r];
+    }
     return;
   }
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-      const int gn = n0 + wn + j * 32 + (lane & 31);
+      const int gn = n0 + wn + j * 32 + ecol;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int gm = m0 + wm + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (gm < M && gn < N) store_out<bf16_t, EPI>(out, (size_t)gm * ldo + gn, acc[i][j][r]);
+        const int gm = erow + i * 32 + 8 * (r >> 2) + (r & 3);
+        if (inside || (gm < M && gn < N)) store_out<bf16_t, EPI>(out, (size_t)gm * ldo + gn, acc[i][j][r]);
       }
     }
 #endif
 }
 
 template <int BM, int EPI>
-static bool launch_pipe_epi(hipStream_t s, const bf16_t *a, const bf16_t *w, int N, int K, Rows rows, void *out, int ldo, int tiles_m, int tiles_n) {
+static bool launch_pipe_epi(hipStream_t s, const bf16_t *a, const bf16_t *w, int N, int K, Rows rows, void *out, int ldo, int tiles_m, int tiles_n, Warm warm) {
   constexpr int kLds = 2 * (BM + 256) * 128;
   static bool ready = false;             // the dynamic LDS size has to be allowed once per kernel
   if (!ready) {
@@ -386,19 +441,19 @@ static bool launch_pipe_epi(hipStream_t s, const bf16_t *a, const bf16_t *w, int
     ready = true;
   }
   const int grid = ((tiles_m * tiles_n + 7) / 8) * 8;
-  k_gemm_pipe<BM, EPI><<<grid, 512, kLds, s>>>(a, w, N, K, rows, out, ldo, tiles_m, tiles_n);
+  k_gemm_pipe<BM, EPI><<<grid, 512, kLds, s>>>(a, w, N, K, rows, out, ldo, tiles_m, tiles_n, warm.ptr, (unsigned)std::min<size_t>(warm.bytes, 0x7fffffffu));
   return true;
 }
 
 template <int BM>
-static bool launch_pipe(hipStream_t s, const void *A, const void *W, int N, int K, Rows rows, int epi, void *out, int ldo) {
+static bool launch_pipe(hipStream_t s, const void *A, const void *W, int N, int K, Rows rows, int epi, void *out, int ldo, Warm warm) {
   const int tiles_m = (rows.cap + BM - 1) / BM;
   const int tiles_n = epi == EPI_SILU_MUL ? (N / 2 + 127) / 128 : (N + 255) / 256;
   const bf16_t *a = (const bf16_t *)A, *w = (const bf16_t *)W;
-  if (epi == EPI_SILU_MUL) return launch_pipe_epi<BM, EPI_SILU_MUL>(s, a, w, N, K, rows, out, ldo, tiles_m, tiles_n);
-  if (epi == EPI_STORE) return launch_pipe_epi<BM, EPI_STORE>(s, a, w, N, K, rows, out, ldo, tiles_m, tiles_n);
-  if (epi == EPI_ADD_F32) return launch_pipe_epi<BM, EPI_ADD_F32>(s, a, w, N, K, rows, out, ldo, tiles_m, tiles_n);
-  return launch_pipe_epi<BM, EPI_STORE_F32>(s, a, w, N, K, rows, out, ldo, tiles_m, tiles_n);
+  if (epi == EPI_SILU_MUL) return launch_pipe_epi<BM, EPI_SILU_MUL>(s, a, w, N, K, rows, out, ldo, tiles_m, tiles_n, warm);
+  if (epi == EPI_STORE) return launch_pipe_epi<BM, EPI_STORE>(s, a, w, N, K, rows, out, ldo, tiles_m, tiles_n, warm);
+  if (epi == EPI_ADD_F32) return launch_pipe_epi<BM, EPI_ADD_F32>(s, a, w, N, K, rows, out, ldo, tiles_m, tiles_n, warm);
+  return launch_pipe_epi<BM, EPI_STORE_F32>(s, a, w, N, K, rows, out, ldo, tiles_m, tiles_n, warm);
 }
 
 bool gemm_fuses_silu_mul(int dtype, const void *A, const void *W, int N, int K) {
@@ -406,7 +461,7 @@ bool gemm_fuses_silu_mul(int dtype, const void *A, const void *W, int N, int K) 
 }
 
 void gemm(hipStream_t s, int dtype, const void *A, const void *W, int N, int K, Rows rows, int epilogue,
-          void *out, int ldo) {
+          void *out, int ldo, Warm warm) {
   if (rows.cap <= 0) return;
   if (dtype == FOCUS_F32) { launch_valu<float>(s, A, W, N, K, rows, epilogue, out, ldo); return; }
   const bool aligned = K % 64 == 0 && ((uintptr_t)A & 15) == 0 && ((uintptr_t)W & 15) == 0;
@@ -417,8 +472,8 @@ void gemm(hipStream_t s, int dtype, const void *A, const void *W, int N, int K, 
   const bool fits32 = (double)std::max(rows.cap + 256, N + 256) * K * 2 < 4.0e9 && (K / 64) % 2 == 0;
   const long t256 = (long)((rows.cap + 255) / 256) * n_tiles, t128 = (long)((rows.cap + 127) / 128) * n_tiles;
   const int choice = t256 >= 160 ? 256 : (t128 >= 160 ? 128 : 0);
-  if (fits32 && choice == 256 && launch_pipe<256>(s, A, W, N, K, rows, epilogue, out, ldo)) return;
-  if (fits32 && choice == 128 && launch_pipe<128>(s, A, W, N, K, rows, epilogue, out, ldo)) return;
+  if (fits32 && choice == 256 && launch_pipe<256>(s, A, W, N, K, rows, epilogue, out, ldo, warm)) return;
+  if (fits32 && choice == 128 && launch_pipe<128>(s, A, W, N, K, rows, epilogue, out, ldo, warm)) return;
   const long tiles_big = (long)((rows.cap + 255) / 256) * ((N + 127) / 128);
   if (tiles_big >= 512) launch_mfma<256, 128>(s, A, W, N, K, rows, epilogue, out, ldo);
   else launch_mfma<128, 128>(s, A, W, N, K, rows, epilogue, out, ldo);
