@@ -150,6 +150,7 @@ class Workload:
     alpha: float = 1.5
     constraints: int = 0        # bit0 AR-context, bit1 placeholder integrity
     conf_threshold: float = 0.9
+    intra_block_cache: int = 0  # 1 = delayed intra-block K/V cache with the neighbour-aware stability criterion
     steps: int = 1
     shuffle_pages: bool = False
     extra_blocks: int = 0       # further blocks each sequence will generate (pages and positions are planned for them)

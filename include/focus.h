@@ -73,6 +73,10 @@ typedef struct focus_config {
   float   alpha;            /* FOCUS_BUDGET_DYNAMIC: expansion factor of Eq. 4 */
   int32_t constraints;      /* FOCUS_KEEP_* bits (Sec. 4.2) */
   float   conf_threshold;   /* commit when confidence >= threshold */
+  int32_t intra_block_cache;/* 1: delayed intra-block K/V cache with the neighbour-aware stability criterion (Sec. 4.3,
+                               App. E.3.1): a position whose token and right neighbour were decoded before a step it
+                               took part in keeps that step's K/V in every layer from then on and leaves the rows of
+                               all later steps of the block; decoded positions not yet frozen are always retained */
 } focus_config;
 
 /* Device pointers.  The per-layer members are HOST arrays of n_layers device pointers. */
@@ -103,7 +107,8 @@ typedef struct focus_step_out {
   int32_t  *row_map;        /* [n * B]  first T' entries valid */
   float    *conf;           /* [n * B]  first T' entries valid: probability of the arg-max token */
   int32_t  *argmax;         /* [n * B]  first T' entries valid */
-  float    *hidden_full;    /* [n * B, hidden]  residual stream entering layer e */
+  float    *hidden_full;    /* [n * B, hidden]  residual stream entering layer e: row b * B + p, or, with the
+                               intra-block cache, the rows of the positions that are not frozen, packed in batch order */
   float    *hidden_packed;  /* [n * B, hidden]  first T' rows valid: residual stream after the last layer */
   float    *logits;         /* [n * B, vocab]   first T' rows valid */
 } focus_step_out;
@@ -115,6 +120,7 @@ typedef struct focus_seq_state {
   int64_t  token_sum;
   uint64_t mask_bits;
   uint64_t processed_bits;  /* positions that have K/V in the layers above e */
+  uint64_t cached_bits;     /* positions whose K/V is frozen in every layer (intra_block_cache) */
   int32_t  tokens[FOCUS_MAX_BLOCK];
 } focus_seq_state;
 

@@ -366,7 +366,7 @@ def _project_qkv(cfg: OracleConfig, w: Dict[str, np.ndarray], X: np.ndarray, abs
 
 
 def _finish_layer(cfg: OracleConfig, w: Dict[str, np.ndarray], X: np.ndarray, attn: np.ndarray) -> np.ndarray:
-    X = X + attn.reshape(X.shape[0], -1) @ w["w_o"].T
+    X = X + attn.reshape(X.shape[0], cfg.n_q_heads * cfg.head_dim) @ w["w_o"].T      # explicit width: a step may have no rows
     u = rmsnorm(X, w["mlp_norm"], cfg.rms_eps)
     gu = u @ w["w_gate_up"].T
     act = silu(gu[:, :cfg.ffn]) * gu[:, cfg.ffn:]

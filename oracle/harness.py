@@ -20,7 +20,7 @@ def oracle_config(wl: Workload, **over) -> fo.OracleConfig:
         mask_token_id=wl.mask_token_id, page_size=wl.page_size, rms_eps=wl.rms_eps, rope_base=wl.rope_base,
         evict_layer=wl.evict_layer, importance_mode=wl.importance_mode, maxpool_k=wl.maxpool_k,
         budget_mode=wl.budget_mode, topk=wl.topk, keep_ratio=wl.keep_ratio, alpha=wl.alpha,
-        constraints=wl.constraints, conf_threshold=wl.conf_threshold)
+        constraints=wl.constraints, conf_threshold=wl.conf_threshold, intra_block_cache=wl.intra_block_cache)
     for k, v in over.items():
         setattr(cfg, k, v)
     return cfg

@@ -30,7 +30,7 @@ class focus_config(C.Structure):
                                          "n_pages", "evict_layer", "importance_mode", "maxpool_k", "budget_mode",
                                          "topk")] + \
                [("keep_ratio", C.c_float), ("alpha", C.c_float), ("constraints", C.c_int32),
-                ("conf_threshold", C.c_float)]
+                ("conf_threshold", C.c_float), ("intra_block_cache", C.c_int32)]
 
 
 class focus_weights(C.Structure):
@@ -48,7 +48,8 @@ class focus_step_out(C.Structure):
 
 class focus_seq_state(C.Structure):
     _fields_ = [("prefix_len", C.c_int32), ("total_steps", C.c_int32), ("token_sum", C.c_int64),
-                ("mask_bits", C.c_uint64), ("processed_bits", C.c_uint64), ("tokens", C.c_int32 * FOCUS_MAX_BLOCK)]
+                ("mask_bits", C.c_uint64), ("processed_bits", C.c_uint64), ("cached_bits", C.c_uint64),
+                ("tokens", C.c_int32 * FOCUS_MAX_BLOCK)]
 
 
 class FocusError(RuntimeError):

@@ -18,11 +18,11 @@ constexpr int kMaxTimed = 4096;
 constexpr int kTargetAttnGroups = 2048;   // (sequence, kv head, split) workgroups the attention launch aims for
 
 struct Plan {
-  size_t off_prefix_len, off_page_count, off_page_table, off_tokens, off_mask, off_processed, off_token_sum, off_total_steps;
+  size_t off_prefix_len, off_page_count, off_page_table, off_tokens, off_mask, off_processed, off_cached, off_token_sum, off_total_steps;
   size_t off_rope, off_resid, off_resid_p, off_normed, off_qkv, off_q_p, off_attn, off_gate_up, off_act, off_logits;
   size_t off_partial, off_delta, off_K, off_keep, off_n_keep, off_vis, off_cu, off_cu_full, off_row_map,
       off_row_map_full, off_total, off_total_full, off_conf, off_argmax, off_prompt, off_prompt_off, off_prompt_len,
-      off_slot_list, off_part_o, off_part_ml, off_order;
+      off_slot_list, off_part_o, off_part_ml, off_order, off_uncached, off_finalized;
   size_t bytes, part_entries;
   int table_stride, max_rows, max_pos;
 };
@@ -44,6 +44,7 @@ Plan make_plan(const focus_config &c) {
   p.off_tokens = take(rows * 4);
   p.off_mask = take(nb * 8);
   p.off_processed = take(nb * 8);
+  p.off_cached = take(nb * 8);
   p.off_token_sum = take(nb * 8);
   p.off_total_steps = take(nb * 4);
   p.off_rope = take((size_t)p.max_pos * (c.head_dim / 2) * sizeof(float2));
@@ -80,6 +81,8 @@ Plan make_plan(const focus_config &c) {
   p.off_part_o = take(p.part_entries * c.head_dim * 4);
   p.off_part_ml = take(p.part_entries * 2 * 4);
   p.off_order = take(nb * 4);
+  p.off_uncached = take(nb * 8);
+  p.off_finalized = take(nb * 4);
   p.bytes = at;
   return p;
 }
@@ -100,6 +103,7 @@ const char *check_config(const focus_config &c) {
   if (c.maxpool_k != 1 && c.maxpool_k != 3) return "maxpool_k must be 1 or 3";
   if (c.budget_mode < 0 || c.budget_mode > 3) return "unknown budget_mode";
   if (c.constraints & ~3) return "unknown constraint bits";
+  if (c.intra_block_cache != 0 && c.intra_block_cache != 1) return "intra_block_cache must be 0 or 1";
   if (!(c.rms_eps > 0.f) || !(c.rope_base > 1.f)) return "rms_eps must be > 0 and rope_base > 1";
   return nullptr;
 }
@@ -127,7 +131,7 @@ struct focus_ctx {
     return {at<int32_t>(plan.off_prefix_len), at<int32_t>(plan.off_page_table), plan.table_stride,
             at<int32_t>(plan.off_tokens), at<uint64_t>(plan.off_mask), at<uint64_t>(plan.off_processed),
             at<int64_t>(plan.off_token_sum), at<int32_t>(plan.off_total_steps), cfg.max_batch,
-            at<int32_t>(plan.off_page_count), cfg.max_prefix_len};
+            at<int32_t>(plan.off_page_count), cfg.max_prefix_len, at<uint64_t>(plan.off_cached)};
   }
   fk::KvLayer kv_layer(int l) const {
     size_t layer_bytes = (size_t)cfg.n_pages * 2 * cfg.n_kv_heads * cfg.page_size * cfg.head_dim * esize(cfg.dtype);
@@ -257,7 +261,7 @@ int fixed_budget(const focus_config &g) {
 
 // Upper bound of the packed row count that the host can know without reading the device.
 int packed_cap(const focus_config &g, int n_seq, bool overridden) {
-  if (overridden || g.constraints || g.budget_mode >= FOCUS_BUDGET_DYNAMIC) return n_seq * g.block_size;
+  if (overridden || g.constraints || g.intra_block_cache || g.budget_mode >= FOCUS_BUDGET_DYNAMIC) return n_seq * g.block_size;
   int k = fixed_budget(g);
   k = k < 0 ? 0 : (k > g.block_size ? g.block_size : k);
   return n_seq * k;
@@ -383,6 +387,7 @@ int focus_get_state(focus_ctx *ctx, int32_t slot, focus_seq_state *st) {
   HIP_TRY(ctx, hipMemcpy(&st->token_sum, s.token_sum + slot, 8, hipMemcpyDeviceToHost));
   HIP_TRY(ctx, hipMemcpy(&st->mask_bits, s.mask_bits + slot, 8, hipMemcpyDeviceToHost));
   HIP_TRY(ctx, hipMemcpy(&st->processed_bits, s.processed_bits + slot, 8, hipMemcpyDeviceToHost));
+  HIP_TRY(ctx, hipMemcpy(&st->cached_bits, s.cached_bits + slot, 8, hipMemcpyDeviceToHost));
   HIP_TRY(ctx, hipMemcpy(st->tokens, s.tokens + (size_t)slot * B, 4 * B, hipMemcpyDeviceToHost));
   return FOCUS_OK;
 }
@@ -402,6 +407,7 @@ int focus_set_state(focus_ctx *ctx, int32_t slot, const focus_seq_state *st) {
   HIP_TRY(ctx, hipMemcpy(s.token_sum + slot, &st->token_sum, 8, hipMemcpyHostToDevice));
   HIP_TRY(ctx, hipMemcpy(s.mask_bits + slot, &st->mask_bits, 8, hipMemcpyHostToDevice));
   HIP_TRY(ctx, hipMemcpy(s.processed_bits + slot, &st->processed_bits, 8, hipMemcpyHostToDevice));
+  HIP_TRY(ctx, hipMemcpy(s.cached_bits + slot, &st->cached_bits, 8, hipMemcpyHostToDevice));
   HIP_TRY(ctx, hipMemcpy(s.tokens + (size_t)slot * B, st->tokens, 4 * B, hipMemcpyHostToDevice));
   return FOCUS_OK;
 }
@@ -515,16 +521,25 @@ int focus_step(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32_t *s
   float *logits = o.logits ? o.logits : ctx->at<float>(pl.off_logits);
 
   // phase 1: whole block through layers 0 .. e-1, layer e up to its K/V fill, importance of layers e-1 and e
-  RowSet full{{T0, nullptr}, {ctx->at<int32_t>(pl.off_row_map_full), seq_slot, B}, n_seq, ctx->at<int32_t>(pl.off_cu_full), B, ctx->at<int32_t>(pl.off_order)};
+  // rows of the layers up to e: every block position, or, with the delayed intra-block cache, those not frozen
+  const bool dc = g.intra_block_cache != 0;
+  uint64_t *uncached = ctx->at<uint64_t>(pl.off_uncached);
+  int32_t *cu_full = ctx->at<int32_t>(pl.off_cu_full), *total_full = ctx->at<int32_t>(pl.off_total_full);
+  RowSet full{{T0, dc ? total_full : nullptr}, {ctx->at<int32_t>(pl.off_row_map_full), seq_slot, B}, n_seq, cu_full, B, ctx->at<int32_t>(pl.off_order)};
   { Timed t(ctx, s, FOCUS_KC_POINTWISE);
-    fk::iota_rows(s, ctx->at<int32_t>(pl.off_row_map_full), ctx->at<int32_t>(pl.off_cu_full), n_seq, B, ctx->at<int32_t>(pl.off_total_full));
+    if (dc) {
+      fk::uncached_bits(s, n_seq, B, seq_slot, st, uncached);
+      fk::scan_compact(s, n_seq, B, uncached, cu_full, ctx->at<int32_t>(pl.off_row_map_full), total_full);
+    } else {
+      fk::iota_rows(s, ctx->at<int32_t>(pl.off_row_map_full), cu_full, n_seq, B, total_full);
+    }
     fk::length_order(s, n_seq, seq_slot, st, ctx->at<int32_t>(pl.off_order));
     fk::embed(s, g.dtype, ctx->embed, g.hidden, full.rows, full.ri, st, g.mask_token_id, resid); }
   for (int l = 0; l < e; ++l) {
     layer_qkv(ctx, s, l, full, resid);
     if (l == e - 1 && g.importance_mode == 0) {
       Timed t(ctx, s, FOCUS_KC_EVICT);
-      fk::importance(s, g.dtype, qkv, n_seq, B, g.n_q_heads, g.n_kv_heads, g.head_dim, g.maxpool_k, partial);
+      fk::importance(s, g.dtype, qkv, cu_full, n_seq, B, g.n_q_heads, g.n_kv_heads, g.head_dim, g.maxpool_k, seq_slot, st, ctx->kv_layer(l), partial);
     }
     layer_rest(ctx, s, l, full, resid, qkv, qkv_w, nullptr);
   }
@@ -535,13 +550,14 @@ int focus_step(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32_t *s
   // phase 2 + 3a: delta, budget, selection, packing, gather
   {
     Timed t(ctx, s, FOCUS_KC_EVICT);
-    fk::importance(s, g.dtype, qkv, n_seq, B, g.n_q_heads, g.n_kv_heads, g.head_dim, g.maxpool_k, partial + partial_stride);
+    fk::importance(s, g.dtype, qkv, cu_full, n_seq, B, g.n_q_heads, g.n_kv_heads, g.head_dim, g.maxpool_k, seq_slot, st, ctx->kv_layer(e),
+                   partial + partial_stride);
     fk::SelectArgs a{};
     a.n_seq = n_seq; a.B = B; a.n_q_heads = g.n_q_heads;
     a.partial_prev = partial; a.partial_evict = partial + partial_stride; a.delta_in = nullptr;
     a.importance_mode = g.importance_mode; a.budget_mode = g.budget_mode; a.K_fixed = fixed_budget(g);
     a.constraints = g.constraints; a.alpha = g.alpha; a.k_override = k_override; a.keep_override = keep_override;
-    a.seq_slot = seq_slot; a.st = st; a.update_state = 1;
+    a.seq_slot = seq_slot; a.st = st; a.update_state = 1; a.intra_block_cache = g.intra_block_cache;
     a.imp_prev_out = o.importance_prev; a.imp_out = o.importance;
     a.delta_out = o.delta_I ? o.delta_I : ctx->at<float>(pl.off_delta);
     a.K_out = o.K ? o.K : ctx->at<int32_t>(pl.off_K);
@@ -552,7 +568,7 @@ int focus_step(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32_t *s
   const int cap = packed_cap(g, n_seq, keep_override != nullptr);
   RowSet packed{{cap, total}, {row_map, seq_slot, B}, n_seq, cu, n_seq > 0 ? (cap + n_seq - 1) / n_seq : 0, ctx->at<int32_t>(pl.off_order)};
   { Timed t(ctx, s, FOCUS_KC_EVICT);
-    fk::gather_rows(s, g.dtype, packed.rows, row_map, resid, resid_p, g.hidden, qkv, qkv_w, q_p, q_w); }
+    fk::gather_rows(s, g.dtype, packed.rows, row_map, B, cu_full, dc ? uncached : nullptr, resid, resid_p, g.hidden, qkv, qkv_w, q_p, q_w); }
 
   // phase 3b: rest of layer e (all B fresh keys of layer e are visible), then the layers above on packed rows
   layer_rest(ctx, s, e, packed, resid_p, q_p, q_w, nullptr);
@@ -570,7 +586,7 @@ int focus_step(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32_t *s
   {
     Timed t(ctx, s, FOCUS_KC_DECODE);
     fk::confidence(s, logits, g.vocab, packed.rows, conf, amax);
-    fk::CommitArgs ca{n_seq, B, seq_slot, st, keep, cu, conf, amax, g.conf_threshold, g.mask_token_id, o.tokens, o.mask_bits, o.n_decoded};
+    fk::CommitArgs ca{n_seq, B, seq_slot, st, keep, cu, conf, amax, g.conf_threshold, g.mask_token_id, g.intra_block_cache, o.tokens, o.mask_bits, o.n_decoded};
     fk::commit(s, ca);
   }
   HIP_TRY(ctx, hipGetLastError());
@@ -591,7 +607,7 @@ int focus_select_compact(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const 
   a.delta_in = delta_I;
   a.importance_mode = g.importance_mode; a.budget_mode = g.budget_mode; a.K_fixed = fixed_budget(g);
   a.constraints = g.constraints; a.alpha = g.alpha; a.k_override = k_override; a.keep_override = nullptr;
-  a.seq_slot = seq_slot; a.st = ctx->slots(); a.update_state = 0;
+  a.seq_slot = seq_slot; a.st = ctx->slots(); a.update_state = 0; a.intra_block_cache = g.intra_block_cache;
   a.delta_out = nullptr; a.K_out = out->K; a.keep_out = out->keep_bits;
   a.n_keep_out = ctx->at<int32_t>(ctx->plan.off_n_keep); a.vis_out = nullptr;
   fk::select(s, a);
@@ -640,15 +656,17 @@ int focus_finalize_blocks(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const
   float *resid = ctx->at<float>(pl.off_resid_p);
   // the prefixes may grow by one block: keep the host-side bound the attention launch is sized with
   ctx->max_total = std::min(ctx->max_total + B, g.max_prefix_len + B);
-  fk::finalize_pick(s, n_seq, B, g.page_size, seq_slot, st, keep, finalized);
+  int32_t *done = ctx->at<int32_t>(pl.off_finalized);
+  fk::finalize_pick(s, n_seq, B, g.page_size, seq_slot, st, keep, done);
+  if (finalized) HIP_TRY(ctx, hipMemcpyAsync(finalized, done, (size_t)n_seq * 4, hipMemcpyDeviceToDevice, s));
   fk::scan_compact(s, n_seq, B, keep, cu, row_map, total);
   RowSet rs{{n_seq * B, total}, {row_map, seq_slot, B}, n_seq, cu, B, nullptr};
   fk::embed(s, g.dtype, ctx->embed, g.hidden, rs.rows, rs.ri, st, g.mask_token_id, resid);
   for (int l = 0; l < g.n_layers; ++l) {
     layer_qkv(ctx, s, l, rs, resid);
-    layer_rest(ctx, s, l, rs, resid, ctx->at<char>(pl.off_qkv), qkv_w, keep);
+    layer_rest(ctx, s, l, rs, resid, ctx->at<char>(pl.off_qkv), qkv_w, nullptr);   // a finished block sees all of itself
   }
-  fk::finalize_advance(s, n_seq, B, seq_slot, st, keep, g.mask_token_id);
+  fk::finalize_advance(s, n_seq, B, seq_slot, st, done, g.mask_token_id);
   HIP_TRY(ctx, hipGetLastError());
   return FOCUS_OK;
 }
@@ -662,7 +680,7 @@ int focus_commit(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32_t 
   static const focus_step_out none{};
   const focus_step_out &o = out ? *out : none;
   fk::CommitArgs ca{n_seq, g.block_size, seq_slot, ctx->slots(), keep_bits, cu_seqlens, conf, argmax, g.conf_threshold,
-                    g.mask_token_id, o.tokens, o.mask_bits, o.n_decoded};
+                    g.mask_token_id, g.intra_block_cache, o.tokens, o.mask_bits, o.n_decoded};
   fk::commit((hipStream_t)hip_stream, ca);
   HIP_TRY(ctx, hipGetLastError());
   return FOCUS_OK;

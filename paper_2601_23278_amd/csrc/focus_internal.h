@@ -33,6 +33,7 @@ struct SlotState {
   int32_t max_batch;
   int32_t *page_count;    // pages each slot's table really holds
   int32_t max_prefix_len;
+  uint64_t *cached_bits;  // positions whose K/V is frozen in every layer (delayed intra-block cache, Sec. 4.3)
 };
 
 // Slot of batch entry b.  A caller-supplied slot list lives in device memory and cannot be checked on the
@@ -111,9 +112,13 @@ struct AttnArgs {
   Warm warm;                     // weights of the projection that follows (bf16 kernel only)
 };
 void attention(hipStream_t s, const AttnArgs &a);
-// Eq. 2 per (sequence, query head) on the full-block qkv buffer: partial[b, h, j].
-void importance(hipStream_t s, int dtype, const void *qkv, int n_seq, int B, int n_q_heads, int n_kv_heads,
-                int head_dim, int maxpool_k, float *partial);
+// Eq. 2 per (sequence, query head): partial[b, h, j] = sum over the sequence's query rows (rows cu[b] .. cu[b + 1] of the
+// fused qkv buffer, after the rotary embedding) of the pooled block-local softmax over the B in-block keys, which
+// are read from the layer's K cache (every row's key has been written there; frozen positions keep theirs).
+void importance(hipStream_t s, int dtype, const void *qkv, const int32_t *cu, int n_seq, int B, int n_q_heads, int n_kv_heads,
+                int head_dim, int maxpool_k, const int32_t *seq_slot, SlotState st, KvLayer kv, float *partial);
+// bits[b] = block positions of batch entry b that are not frozen
+void uncached_bits(hipStream_t s, int n_seq, int B, const int32_t *seq_slot, SlotState st, uint64_t *bits);
 struct SelectArgs {
   int n_seq, B, n_q_heads;
   const float *partial_prev, *partial_evict;   // [n, Hq, B] or null (then delta_in is used)
@@ -124,6 +129,7 @@ struct SelectArgs {
   const uint64_t *keep_override;
   const int32_t *seq_slot;
   SlotState st;
+  int intra_block_cache;                       // Sec. 4.3: frozen positions are never retained, decoded unfrozen ones always
   int update_state;                            // processed_bits |= keep
   float *imp_prev_out, *imp_out, *delta_out;   // [n, B] or null
   int32_t *K_out;
@@ -135,8 +141,10 @@ void select(hipStream_t s, const SelectArgs &a);
 // cu[b] = exclusive prefix sum of n_keep, row_map, cu[n] also to *total.
 void scan_compact(hipStream_t s, int n_seq, int B, const uint64_t *keep_bits, int32_t *cu, int32_t *row_map,
                   int32_t *total);
-void gather_rows(hipStream_t s, int dtype, Rows rows, const int32_t *row_map, const float *resid, float *resid_p,
-                 int hidden, const void *qkv, int qkv_stride, void *q_p, int q_width);
+// Packed row r = (b, p) is copied from row src_cu[b] + (number of src_bits[b] below p) of the source buffers
+// (src_bits null: from row b * B + p).
+void gather_rows(hipStream_t s, int dtype, Rows rows, const int32_t *row_map, int B, const int32_t *src_cu, const uint64_t *src_bits,
+                 const float *resid, float *resid_p, int hidden, const void *qkv, int qkv_stride, void *q_p, int q_width);
 void silu_mul(hipStream_t s, int dtype, const void *gate_up, void *act, int ffn, Rows rows);
 void confidence(hipStream_t s, const float *logits, int vocab, Rows rows, float *conf, int32_t *argmax);
 struct CommitArgs {
@@ -149,6 +157,7 @@ struct CommitArgs {
   const int32_t *argmax;
   float threshold;
   int mask_id;
+  int intra_block_cache;     // freeze positions by the neighbour-aware stability criterion (Sec. 4.3)
   int32_t *tokens_out;       // [n, B] or null
   uint64_t *mask_out;
   int32_t *n_decoded_out;
@@ -164,7 +173,7 @@ void reset_block_state(hipStream_t s, int n_seq, int B, const int32_t *seq_slot,
 // and, after their last forward, turns the block into prefix and starts a new all-masked block.
 void finalize_pick(hipStream_t s, int n_seq, int B, int page_size, const int32_t *seq_slot, SlotState st, uint64_t *keep_bits,
                    int32_t *finalized);
-void finalize_advance(hipStream_t s, int n_seq, int B, const int32_t *seq_slot, SlotState st, const uint64_t *keep_bits, int mask_id);
+void finalize_advance(hipStream_t s, int n_seq, int B, const int32_t *seq_slot, SlotState st, const int32_t *finalized, int mask_id);
 void fill_u64(hipStream_t s, uint64_t *p, int n, uint64_t v);
 void iota_rows(hipStream_t s, int32_t *row_map, int32_t *cu, int n_seq, int B, int32_t *total);
 // order[rank] = batch entry, ranked by descending prefix length (ties: lower entry first)

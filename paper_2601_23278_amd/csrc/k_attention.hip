@@ -344,24 +344,47 @@ void attention(hipStream_t s, const AttnArgs &a) {
 // Token importance, Eq. 2: for one (sequence, query head), S_ij = q_i . k_j / sqrt(D) over the block's own
 // B x B scores, MaxPool1D (window 3, same length) along j, softmax along j, column sums over i.
 // Output partial[b, h, j]; the head sum is taken later in a fixed order (no atomics, so it is reproducible).
-// The fused qkv buffer of the full block is read after the rotary embedding has been applied in place.
+// Queries: the sequence's rows of the fused qkv buffer (after the rotary embedding), i.e. all B positions, or, with the
+// delayed intra-block cache (Sec. 4.3), the positions that are not frozen.  Keys: the B block positions of the layer's
+// K cache, which holds the key every row just wrote and the frozen positions' keys.
+struct ImpArgs {
+  const void *qkv;
+  const int32_t *cu;       // query rows of batch entry b: cu[b] .. cu[b + 1]
+  int B, Hq, Hkv, D, pool_k;
+  const int32_t *seq_slot;
+  SlotState st;
+  KvLayer kv;
+  float *partial;
+};
+
+// K cache row of block position j of the sequence in slot `slot`, kv head hk
+template <typename T>
+__device__ __forceinline__ const T *block_key_row(const ImpArgs &a, int slot, int hk, int j) {
+  const int P = a.kv.page_size, pos = a.st.prefix_len[slot] + j;
+  const int page = a.st.page_table[(size_t)slot * a.st.table_stride + pos / P];
+  return (const T *)a.kv.base + (size_t)page * 2 * a.Hkv * P * a.D + ((size_t)hk * P + pos % P) * a.D;
+}
+
 template <typename T, int MAXB, int MAXD>
-__global__ __launch_bounds__(256) void k_importance(const T *__restrict__ qkv, int B, int Hq, int Hkv, int D, int pool_k,
-                                                    float *partial) {
+__global__ __launch_bounds__(256) void k_importance(ImpArgs a) {
   __shared__ float ks[MAXB * (MAXD + 1)];
   __shared__ float S[MAXB][MAXB + 1];
+  const int B = a.B, Hq = a.Hq, Hkv = a.Hkv, D = a.D, pool_k = a.pool_k;
+  float *partial = a.partial;
   const int b = blockIdx.x, h = blockIdx.y, hk = h / (Hq / Hkv);
+  const int slot = slot_of(a.seq_slot, b, a.st);
   const int stride = (Hq + 2 * Hkv) * D;
-  const T *base = qkv + (size_t)b * B * stride;
+  const int r0 = a.cu[b], nq = min(a.cu[b + 1] - r0, B);
+  const T *base = (const T *)a.qkv + (size_t)r0 * stride;
   for (int i = threadIdx.x; i < B * D; i += 256) {
     int j = i / D, d = i % D;
-    ks[j * (D + 1) + d] = to_f(base[(size_t)j * stride + (size_t)(Hq + hk) * D + d]);
+    ks[j * (D + 1) + d] = to_f(block_key_row<T>(a, slot, hk, j)[d]);
   }
   __syncthreads();
   const float scale = 1.0f / sqrtf((float)D);
   // thread -> query row i = tid / 4 and keys j = (tid % 4) + 4 * jj
   const int i = threadIdx.x >> 2, j0 = threadIdx.x & 3;
-  if (i < B) {
+  if (i < nq) {
     float acc[MAXB / 4];
     for (int jj = 0; jj < MAXB / 4; ++jj) acc[jj] = 0.f;
     const T *qi = base + (size_t)i * stride + (size_t)h * D;
@@ -386,7 +409,7 @@ __global__ __launch_bounds__(256) void k_importance(const T *__restrict__ qkv, i
     }
   }
   __syncthreads();
-  if ((int)threadIdx.x < B) {
+  if ((int)threadIdx.x < nq) {
     const int row = threadIdx.x;
     float m = -INFINITY;                        // max of the pooled row equals max of the row
     for (int j = 0; j < B; ++j) m = fmaxf(m, S[row][j]);
@@ -413,7 +436,7 @@ __global__ __launch_bounds__(256) void k_importance(const T *__restrict__ qkv, i
   if ((int)threadIdx.x < B) {
     const int j = threadIdx.x;
     float col = 0.f;
-    for (int ii = 0; ii < B; ++ii) col += S[ii][j];
+    for (int ii = 0; ii < nq; ++ii) col += S[ii][j];
     partial[((size_t)b * Hq + h) * B + j] = col;
   }
 }
@@ -423,18 +446,21 @@ __global__ __launch_bounds__(256) void k_importance(const T *__restrict__ qkv, i
 // so pooling, max, exp and normalisation run in registers; the column sums are 5-step lane reductions, the lower
 // lane half finishing the lower half of the keys and the upper half the rest.
 template <int NJ>   // key tiles of 32: B <= 32 * NJ
-__global__ __launch_bounds__(64) void k_importance_mfma(const bf16_t *__restrict__ qkv, int B, int Hq, int Hkv, int pool_k,
-                                                        float *partial) {
+__global__ __launch_bounds__(64) void k_importance_mfma(ImpArgs a) {
   constexpr int D = 128, BJ = 32 * NJ, HJ = BJ / 2;
+  const int B = a.B, Hq = a.Hq, Hkv = a.Hkv, pool_k = a.pool_k;
+  float *partial = a.partial;
   const int b = blockIdx.x, h = blockIdx.y, hk = h / (Hq / Hkv);
+  const int slot = slot_of(a.seq_slot, b, a.st);
   const int lane = threadIdx.x, half = lane >> 5, col = lane & 31;
   const int stride = (Hq + 2 * Hkv) * D;
-  const bf16_t *base = qkv + (size_t)b * B * stride;
+  const int r0 = a.cu[b], nq = min(a.cu[b + 1] - r0, B);
+  const bf16_t *base = (const bf16_t *)a.qkv + (size_t)r0 * stride;
   const float sc = 1.4426950408889634f / sqrtf((float)D);
   bf16x8 kf[NJ][8];
 #pragma unroll
   for (int jt = 0; jt < NJ; ++jt) {
-    const bf16_t *kp = base + (size_t)min(32 * jt + col, B - 1) * stride + (size_t)(Hq + hk) * D + 8 * half;
+    const bf16_t *kp = block_key_row<bf16_t>(a, slot, hk, min(32 * jt + col, B - 1)) + 8 * half;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) kf[jt][ks] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(kp + 16 * ks));
   }
@@ -442,10 +468,10 @@ __global__ __launch_bounds__(64) void k_importance_mfma(const bf16_t *__restrict
 #pragma unroll
   for (int jj = 0; jj < HJ; ++jj) acc[jj] = 0.f;
 
-  for (int it = 0; it * 32 < B; ++it) {
+  for (int it = 0; it * 32 < nq; ++it) {
     const int i = 32 * it + col;
     bf16x8 qf[8];
-    const bf16_t *qp = base + (size_t)min(i, B - 1) * stride + (size_t)h * D + 8 * half;
+    const bf16_t *qp = base + (size_t)min(i, max(nq - 1, 0)) * stride + (size_t)h * D + 8 * half;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) qf[ks] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(qp + 16 * ks));
     // full score row of query i in every lane: own registers for the keys of this lane half, the partner's for the rest
@@ -484,7 +510,7 @@ __global__ __launch_bounds__(64) void k_importance_mfma(const bf16_t *__restrict
       pooled[j] = exp2f(pooled[j] - m);
       sum += pooled[j];
     }
-    const float inv = i < B ? 1.0f / sum : 0.f;                   // rows beyond the block add nothing
+    const float inv = i < nq ? 1.0f / sum : 0.f;                  // lanes beyond the sequence's rows add nothing
 #pragma unroll
     for (int jj = 0; jj < HJ; ++jj) {
       float v = (half ? pooled[jj + HJ] : pooled[jj]) * inv;
@@ -499,19 +525,18 @@ __global__ __launch_bounds__(64) void k_importance_mfma(const bf16_t *__restrict
   }
 }
 
-void importance(hipStream_t s, int dtype, const void *qkv, int n_seq, int B, int n_q_heads, int n_kv_heads,
-                int head_dim, int maxpool_k, float *partial) {
+void importance(hipStream_t s, int dtype, const void *qkv, const int32_t *cu, int n_seq, int B, int n_q_heads, int n_kv_heads,
+                int head_dim, int maxpool_k, const int32_t *seq_slot, SlotState st, KvLayer kv, float *partial) {
   if (n_seq <= 0) return;
   dim3 grid(n_seq, n_q_heads);
-  if (dtype == FOCUS_BF16 && head_dim == 128 && ((uintptr_t)qkv & 15) == 0) {
-    if (B <= 32) k_importance_mfma<1><<<grid, 64, 0, s>>>((const bf16_t *)qkv, B, n_q_heads, n_kv_heads, maxpool_k, partial);
-    else k_importance_mfma<2><<<grid, 64, 0, s>>>((const bf16_t *)qkv, B, n_q_heads, n_kv_heads, maxpool_k, partial);
+  const ImpArgs a{qkv, cu, B, n_q_heads, n_kv_heads, head_dim, maxpool_k, seq_slot, st, kv, partial};
+  if (dtype == FOCUS_BF16 && head_dim == 128 && (((uintptr_t)qkv | (uintptr_t)kv.base) & 15) == 0) {
+    if (B <= 32) k_importance_mfma<1><<<grid, 64, 0, s>>>(a);
+    else k_importance_mfma<2><<<grid, 64, 0, s>>>(a);
     return;
   }
-  if (dtype == FOCUS_F32)
-    k_importance<float, 64, 128><<<grid, 256, 0, s>>>((const float *)qkv, B, n_q_heads, n_kv_heads, head_dim, maxpool_k, partial);
-  else
-    k_importance<bf16_t, 64, 128><<<grid, 256, 0, s>>>((const bf16_t *)qkv, B, n_q_heads, n_kv_heads, head_dim, maxpool_k, partial);
+  if (dtype == FOCUS_F32) k_importance<float, 64, 128><<<grid, 256, 0, s>>>(a);
+  else k_importance<bf16_t, 64, 128><<<grid, 256, 0, s>>>(a);
 }
 
 }  // namespace fk

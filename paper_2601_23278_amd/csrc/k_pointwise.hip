@@ -208,11 +208,16 @@ void rope_kv_write(hipStream_t s, int dtype, void *qkv, int n_q_heads, Rows rows
 // ---------------------------------------------------------------------------------------------
 // Gather of the retained rows (Sec. 4.2): residual stream and the layer-e queries, into packed order.
 template <typename T>
-__global__ __launch_bounds__(256) void k_gather(Rows rows, const int32_t *row_map, const float *resid, float *resid_p,
-                                                int hidden, const T *qkv, int qkv_stride, T *q_p, int q_width) {
+__global__ __launch_bounds__(256) void k_gather(Rows rows, const int32_t *row_map, int B, const int32_t *src_cu, const uint64_t *src_bits,
+                                                const float *resid, float *resid_p, int hidden, const T *qkv, int qkv_stride, T *q_p,
+                                                int q_width) {
   int r = blockIdx.x;
   if (r >= n_rows(rows)) return;
   int src = row_map[r];
+  if (src_bits) {       // the source rows are themselves a packed subset of the block positions
+    const int b = src / B, p = src % B;
+    src = src_cu[b] + __popcll(src_bits[b] & ((1ull << p) - 1));
+  }
   const float4 *a = (const float4 *)(resid + (size_t)src * hidden);
   float4 *o = (float4 *)(resid_p + (size_t)r * hidden);
   for (int i = threadIdx.x; i < hidden / 4; i += 256) o[i] = a[i];
@@ -221,14 +226,14 @@ __global__ __launch_bounds__(256) void k_gather(Rows rows, const int32_t *row_ma
   for (int i = threadIdx.x; i < q_width; i += 256) qo[i] = q[i];
 }
 
-void gather_rows(hipStream_t s, int dtype, Rows rows, const int32_t *row_map, const float *resid, float *resid_p,
-                 int hidden, const void *qkv, int qkv_stride, void *q_p, int q_width) {
+void gather_rows(hipStream_t s, int dtype, Rows rows, const int32_t *row_map, int B, const int32_t *src_cu, const uint64_t *src_bits,
+                 const float *resid, float *resid_p, int hidden, const void *qkv, int qkv_stride, void *q_p, int q_width) {
   if (rows.cap <= 0) return;
   if (dtype == FOCUS_F32)
-    k_gather<float><<<rows.cap, 256, 0, s>>>(rows, row_map, resid, resid_p, hidden, (const float *)qkv, qkv_stride,
+    k_gather<float><<<rows.cap, 256, 0, s>>>(rows, row_map, B, src_cu, src_bits, resid, resid_p, hidden, (const float *)qkv, qkv_stride,
                                              (float *)q_p, q_width);
   else
-    k_gather<bf16_t><<<rows.cap, 256, 0, s>>>(rows, row_map, resid, resid_p, hidden, (const bf16_t *)qkv, qkv_stride,
+    k_gather<bf16_t><<<rows.cap, 256, 0, s>>>(rows, row_map, B, src_cu, src_bits, resid, resid_p, hidden, (const bf16_t *)qkv, qkv_stride,
                                               (bf16_t *)q_p, q_width);
 }
 
@@ -302,6 +307,7 @@ __global__ void k_reset_block(int n_seq, int B, const int32_t *seq_slot, SlotSta
     st.prefix_len[slot] = prefix_len[b];
     st.mask_bits[slot] = B >= 64 ? ~0ull : ((1ull << B) - 1);
     st.processed_bits[slot] = 0;
+    st.cached_bits[slot] = 0;
     if (!keep_stats) {
       st.token_sum[slot] = 0;
       st.total_steps[slot] = 0;
@@ -320,7 +326,7 @@ __global__ void k_finalize_pick(int n_seq, int B, int P, const int32_t *seq_slot
   const uint64_t all = B >= 64 ? ~0ull : ((1ull << B) - 1);
   const int L = st.prefix_len[slot];
   const bool done = (st.mask_bits[slot] & all) == 0 && L + B <= st.max_prefix_len && (long)L + 2 * B <= (long)st.page_count[slot] * P;
-  keep_bits[b] = done ? all : 0;
+  keep_bits[b] = done ? all & ~st.cached_bits[slot] : 0;      // frozen positions keep the K/V they have (Sec. 4.3)
   if (finalized) finalized[b] = done ? 1 : 0;
 }
 void finalize_pick(hipStream_t s, int n_seq, int B, int page_size, const int32_t *seq_slot, SlotState st, uint64_t *keep_bits,
@@ -328,19 +334,20 @@ void finalize_pick(hipStream_t s, int n_seq, int B, int page_size, const int32_t
   if (n_seq > 0) k_finalize_pick<<<(n_seq + 63) / 64, 64, 0, s>>>(n_seq, B, page_size, seq_slot, st, keep_bits, finalized);
 }
 
-__global__ void k_finalize_advance(int n_seq, int B, const int32_t *seq_slot, SlotState st, const uint64_t *keep_bits, int mask_id) {
+__global__ void k_finalize_advance(int n_seq, int B, const int32_t *seq_slot, SlotState st, const int32_t *finalized, int mask_id) {
   const int b = blockIdx.x;
-  if (keep_bits[b] == 0) return;
+  if (!finalized[b]) return;
   const int slot = slot_of(seq_slot, b, st);
   if ((int)threadIdx.x < B) st.tokens[slot * B + threadIdx.x] = mask_id;
   if (threadIdx.x == 0) {
     st.prefix_len[slot] += B;
     st.mask_bits[slot] = B >= 64 ? ~0ull : ((1ull << B) - 1);
     st.processed_bits[slot] = 0;
+    st.cached_bits[slot] = 0;
   }
 }
-void finalize_advance(hipStream_t s, int n_seq, int B, const int32_t *seq_slot, SlotState st, const uint64_t *keep_bits, int mask_id) {
-  if (n_seq > 0) k_finalize_advance<<<n_seq, 64, 0, s>>>(n_seq, B, seq_slot, st, keep_bits, mask_id);
+void finalize_advance(hipStream_t s, int n_seq, int B, const int32_t *seq_slot, SlotState st, const int32_t *finalized, int mask_id) {
+  if (n_seq > 0) k_finalize_advance<<<n_seq, 64, 0, s>>>(n_seq, B, seq_slot, st, finalized, mask_id);
 }
 
 // Prefill: chunk c of each prompt becomes the (fully unmasked) block at prefix_len = c * B; sequences whose
@@ -355,6 +362,7 @@ __global__ void k_prefill_chunk(int n_seq, int B, int chunk, const int32_t *seq_
   if (threadIdx.x == 0) {
     st.prefix_len[slot] = start;
     st.mask_bits[slot] = 0;
+    st.cached_bits[slot] = 0;
     keep_bits[b] = nr >= 64 ? ~0ull : ((1ull << nr) - 1);
   }
 }

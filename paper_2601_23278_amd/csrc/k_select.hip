@@ -38,6 +38,10 @@ __global__ __launch_bounds__(64) void k_select(SelectArgs a) {
   const uint64_t all = low_bits(B);
   const uint64_t masked = a.st.mask_bits[slot] & all;
   const bool is_masked = (masked >> j) & 1ull;
+  // delayed intra-block cache (Sec. 4.3): frozen positions have left the rows; decoded positions that are not frozen
+  // yet are owed the forward with their final token in every layer
+  const uint64_t frozen = a.intra_block_cache ? a.st.cached_bits[slot] & all : 0ull;
+  const uint64_t owed = a.intra_block_cache ? all & ~frozen & ~masked : 0ull;
   uint64_t keep;
   int K;
 
@@ -78,7 +82,7 @@ __global__ __launch_bounds__(64) void k_select(SelectArgs a) {
     K = max(0, min(B, K));
 
     if (K >= B) {
-      keep = all;                                // no eviction: the whole block stays
+      keep = all & ~frozen;                      // no eviction: the whole block (what is left of it) stays
     } else {
       // rank of position j among the masked positions: number that order before it
       float v = (d != d) ? -INFINITY : d;        // NaN ranks last
@@ -91,12 +95,13 @@ __global__ __launch_bounds__(64) void k_select(SelectArgs a) {
       const uint64_t top = __ballot(in && is_masked && rank < K);
       keep = top;
       if (keep) {
-        if (a.constraints & FOCUS_KEEP_AR_CONTEXT) keep |= top >> 1;          // predecessor of every pick
+        if (a.constraints & FOCUS_KEEP_AR_CONTEXT) keep |= (top >> 1) & ~frozen;   // predecessor of every pick
         if (a.constraints & FOCUS_KEEP_PLACEHOLDERS) {
           int mx = 63 - __clzll((long long)keep);
           keep |= masked & low_bits(mx);                                      // masked positions below max(S)
         }
       }
+      keep |= owed;
     }
   }
   if (j == 0) {
@@ -251,9 +256,16 @@ __global__ __launch_bounds__(64) void k_commit(CommitArgs a) {
     masked &= ~cleared;
     n_dec = __popcll(pass);
     if (i == 0) {
+      const uint64_t before = a.st.mask_bits[slot];
       a.st.mask_bits[slot] = masked;
       a.st.token_sum[slot] += n_dec;
       a.st.total_steps[slot] += 1;
+      if (a.intra_block_cache) {
+        // neighbour-aware stability (Sec. 4.3): a retained position that was decoded before this step, and whose right
+        // neighbour was too (the last position has none), went through this forward with its final context: freeze it
+        const uint64_t all = low_bits(B), unm = all & ~before;
+        a.st.cached_bits[slot] |= keep & unm & ((unm >> 1) | (1ull << (B - 1)));
+      }
     }
   }
   __syncthreads();
@@ -265,6 +277,15 @@ __global__ __launch_bounds__(64) void k_commit(CommitArgs a) {
     if (a.mask_out) a.mask_out[b] = masked;
     if (a.n_decoded_out) a.n_decoded_out[b] = n_dec;
   }
+}
+
+__global__ void k_uncached_bits(int n_seq, int B, const int32_t *seq_slot, SlotState st, uint64_t *bits) {
+  const int b = blockIdx.x * 256 + threadIdx.x;
+  if (b < n_seq) bits[b] = low_bits(B) & ~st.cached_bits[slot_of(seq_slot, b, st)];
+}
+
+void uncached_bits(hipStream_t s, int n_seq, int B, const int32_t *seq_slot, SlotState st, uint64_t *bits) {
+  if (n_seq > 0) k_uncached_bits<<<(n_seq + 255) / 256, 256, 0, s>>>(n_seq, B, seq_slot, st, bits);
 }
 
 void commit(hipStream_t s, const CommitArgs &a) {

@@ -22,6 +22,7 @@ def config_from_workload(wl: Workload, max_batch: int, max_prefix_len: int, n_pa
     c.evict_layer, c.importance_mode, c.maxpool_k = wl.evict_layer, wl.importance_mode, wl.maxpool_k
     c.budget_mode, c.topk, c.keep_ratio, c.alpha = wl.budget_mode, wl.topk, wl.keep_ratio, wl.alpha
     c.constraints, c.conf_threshold = wl.constraints, wl.conf_threshold
+    c.intra_block_cache = wl.intra_block_cache
     return c
 
 

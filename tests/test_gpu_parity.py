@@ -110,8 +110,8 @@ def compare_steps(wl, steps, tol, exact, seq_ids=None, k_override=None):
         e_dI = max(relerr(g["delta_I"][b], tr.delta_I[b]) for b in range(n))
         e_I = max(relerr(g["importance"][b], tr.I_evict[b]) for b in range(n))
         assert e_I <= tol and e_dI <= max(tol, 5 * tol if not exact else tol), (e_I, e_dI)
-        for b in range(n):
-            assert abs(float(g["importance"][b].sum()) - B * wl.n_q_heads) < 1e-2 * B * wl.n_q_heads * tol + 1e-3
+        for b in range(n):      # Eq. 2 sums to (query rows) x H_q: all B positions, or those not frozen (Sec. 4.3)
+            assert abs(float(g["importance"][b].sum()) - len(tr.uncached[b]) * wl.n_q_heads) < 1e-2 * B * wl.n_q_heads * tol + 1e-3
         # decisions
         if exact:
             assert [int(k) for k in g["K"]] == tr.K
@@ -125,7 +125,7 @@ def compare_steps(wl, steps, tol, exact, seq_ids=None, k_override=None):
         T = tr.cu[-1]
         assert [int(x) for x in g["row_map"][:T]] == tr.row_map
         # floats
-        e_hf = relerr(g["hidden_full"], tr.hidden_full)
+        e_hf = relerr(g["hidden_full"][:len(tr.hidden_full)], tr.hidden_full)
         e_hp = relerr(g["hidden_packed"][:T], tr.hidden_packed)
         e_lg = row_relerr(g["logits"][:T], tr.logits)
         e_cf = relerr(g["conf"][:T], np.asarray(tr.conf)) if T else 0.0
@@ -170,6 +170,9 @@ def compare_steps(wl, steps, tol, exact, seq_ids=None, k_override=None):
             s = sess.focus.focus_get_state(b)
             assert (s.token_sum, s.total_steps, s.prefix_len) == (states[b].token_sum, states[b].total_steps, lens[sess.seq_ids[b]])
             assert s.processed_bits == bits_of([p for p in range(B) if states[b].processed[p]])
+            assert s.cached_bits == bits_of([p for p in range(B) if states[b].cached[p]])
+        stats[-1]["frozen"] = sum(sum(st.cached) for st in states)
+        stats[-1]["rows_full"] = len(tr.hidden_full)
     sess.focus.focus_free()
     return stats
 
@@ -211,6 +214,20 @@ def test_c1_variants_fp32_exact(variant):
     compare_steps(wl, wl.steps, 1e-3, exact=True, k_override=ko)
 
 
+def test_c1_intra_block_cache_fp32_exact():
+    """Delayed intra-block K/V cache with the neighbour-aware stability criterion (Sec. 4.3): a low threshold makes
+    several tokens commit per step, so positions freeze, leave the rows of the early layers and keep their K/V."""
+    wl = fi.workload("c1_tiny", intra_block_cache=1, conf_threshold=0.0013, keep_ratio=0.5, steps=7)
+    stats = compare_steps(wl, wl.steps, 1e-3, exact=True)
+    assert stats[-1]["frozen"] > 0 and min(s["rows_full"] for s in stats) < wl.batch * wl.block_size, stats
+
+
+def test_c1_intra_block_cache_with_constraints_and_dynamic_budget():
+    wl = fi.workload("c1_tiny", intra_block_cache=1, conf_threshold=0.0013, budget_mode=2, constraints=3, steps=6)
+    stats = compare_steps(wl, wl.steps, 1e-3, exact=True)
+    assert stats[-1]["frozen"] > 0, stats
+
+
 def small_bf16(**over):
     base = dict(n_layers=3, hidden=512, n_q_heads=8, n_kv_heads=2, ffn=1024, vocab=4096, mask_token_id=4095,
                 batch=5, prefix_lo=70, prefix_hi=200, prefix_dist="uniform", block_size=32, budget_mode=1,
@@ -221,6 +238,11 @@ def small_bf16(**over):
 
 def test_small_bf16_teacher_forced():
     compare_steps(small_bf16(), 3, 2e-2, exact=False)
+
+
+def test_small_bf16_intra_block_cache_teacher_forced():
+    stats = compare_steps(small_bf16(intra_block_cache=1, conf_threshold=0.0004, keep_ratio=0.5, steps=6), 6, 2e-2, exact=False)
+    assert stats[-1]["frozen"] > 0, stats
 
 
 def test_small_bf16_block64_override_empty_and_full():
@@ -354,17 +376,20 @@ def test_step_argument_errors():
     sess.focus.focus_free()
 
 
-def test_multi_block_generation_with_finalize_fp32():
+@pytest.mark.parametrize("intra_block_cache", [0, 1])
+def test_multi_block_generation_with_finalize_fp32(intra_block_cache):
     """Two blocks generated back to back: steps until a block has no masked position, focus_finalize_blocks, next
     block.  Tokens, masks, counters and prefix lengths must equal the oracle's at every step; at the end the whole
-    cache (prompt + both generated blocks, every layer) must equal the oracle's."""
+    cache (prompt + both generated blocks, every layer) must equal the oracle's.  With the delayed intra-block cache
+    (Sec. 4.3) frozen positions take no part in the last forward and keep the K/V they have."""
     pk, runner = _pk()
-    wl = fi.workload("c1_tiny", keep_ratio=0.5, extra_blocks=2)
+    wl = fi.workload("c1_tiny", keep_ratio=0.5, extra_blocks=2, intra_block_cache=intra_block_cache)
     cfg, W, pool, states, lens, tables, n_pages = oracle_batch(wl)
     sess = runner.open_session(wl, DEV)
     n, B = wl.batch, wl.block_size
     outs = Outs(pk, wl, n)
     fin = torch.zeros(n, dtype=torch.int32, device=DEV)
+    frozen_seen = False
     for block in range(2):
         for step in range(B + 1):
             sess.focus.focus_finalize_blocks(n, fin)
@@ -384,12 +409,15 @@ def test_multi_block_generation_with_finalize_fp32():
             for b, st in enumerate(states):
                 assert [int(t) for t in g["tokens"][b]] == st.tokens
                 assert u64(g["mask_bits"][b]) == bits_of([p for p in range(B) if st.masked[p]])
+                assert sess.focus.focus_get_state(b).cached_bits == bits_of([p for p in range(B) if st.cached[p]])
+            frozen_seen = frozen_seen or any(any(st.cached) for st in states)
         else:
             raise AssertionError("block did not finish")
         for b, st in enumerate(states):
             s = sess.focus.focus_get_state(b)
             assert (s.prefix_len, s.token_sum, s.total_steps, s.processed_bits) == (lens[b] + (block + 1) * B, st.token_sum, st.total_steps, 0)
-            assert s.mask_bits == (1 << B) - 1 and st.prefix_len == s.prefix_len
+            assert s.mask_bits == (1 << B) - 1 and st.prefix_len == s.prefix_len and s.cached_bits == 0
+    assert frozen_seen == bool(intra_block_cache)
     kv = sess.kv_pool.cpu().numpy()
     P = wl.page_size
     for l in range(wl.n_layers):
