@@ -196,7 +196,7 @@ void layer_qkv(focus_ctx *c, hipStream_t s, int l, const RowSet &rs, const float
   { Timed t(c, s, FOCUS_KC_POINTWISE); fk::rmsnorm(s, g.dtype, resid, c->attn_norm[l], normed, g.hidden, g.rms_eps, rs.rows); }
   { Timed t(c, s, FOCUS_KC_GEMM); fk::gemm(s, g.dtype, normed, c->w_qkv[l], qkv_w, g.hidden, rs.rows, fk::EPI_STORE, qkv, qkv_w); }
   { Timed t(c, s, FOCUS_KC_POINTWISE);
-    fk::rope_kv_write(s, g.dtype, qkv, g.n_q_heads, rs.rows, rs.ri, c->slots(), c->kv_layer(l), c->at<float2>(c->plan.off_rope)); }
+    fk::rope_kv_write(s, g.dtype, qkv, g.n_q_heads, rs.rows, rs.ri, c->slots(), c->kv_layer(l), c->at<float2>(c->plan.off_rope), rs.n_seq, rs.cu); }
 }
 
 // attention -> O projection (+residual) -> rmsnorm -> gate/up -> SiLU*up -> down (+residual).

@@ -91,8 +91,9 @@ __device__ __forceinline__ unsigned warm_touch(const void *ptr, size_t bytes, in
   return acc;
 }
 // Rotates q and k rows of the fused qkv buffer in place and stores k, v of every row into its cache slot.
+// n_seq, cu: the row range of every batch entry (rows cu[b] .. cu[b + 1]), or 0 / null when not known.
 void rope_kv_write(hipStream_t s, int dtype, void *qkv, int n_q_heads, Rows rows, RowIndex ri, SlotState st,
-                   KvLayer kv, const float2 *rope_table);
+                   KvLayer kv, const float2 *rope_table, int n_seq = 0, const int32_t *cu = nullptr);
 struct AttnArgs {
   int dtype;
   const void *q;                 // [rows, q_stride] rotated queries, head h at column h * D

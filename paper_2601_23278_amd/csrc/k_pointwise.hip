@@ -158,7 +158,7 @@ __global__ __launch_bounds__(256) void k_rope_kv_write(T *qkv, int Hq, Rows rows
 
 // bf16: eight rotation pairs per thread step, 16-byte loads and stores (q, k in place; k also into its cache row).
 __global__ __launch_bounds__(256) void k_rope_kv_write_bf16(bf16_t *qkv, int Hq, Rows rows, RowIndex ri, SlotState st, KvLayer kv,
-                                                            const float2 *rope) {
+                                                            const float2 *rope, int write_v) {
   const int r = blockIdx.x;
   if (r >= n_rows(rows)) return;
   const int D = kv.head_dim, half = D / 2, Hkv = kv.n_kv_heads, P = kv.page_size, upr = half / 8;   // units per head
@@ -187,16 +187,41 @@ __global__ __launch_bounds__(256) void k_rope_kv_write_bf16(bf16_t *qkv, int Hq,
       *(bf16x8_t *)(dst + d + half) = y2;
     }
   }
-  const bf16_t *v = row + (size_t)(Hq + Hkv) * D;
-  bf16_t *vc = cache + (size_t)Hkv * P * D;
-  for (int i = threadIdx.x; i < Hkv * D; i += 256) vc[(size_t)i * P + off] = v[i];   // V transposed: [H_kv][D][page_size]
+  if (write_v) {
+    const bf16_t *v = row + (size_t)(Hq + Hkv) * D;
+    bf16_t *vc = cache + (size_t)Hkv * P * D;
+    for (int i = threadIdx.x; i < Hkv * D; i += 256) vc[(size_t)i * P + off] = v[i];   // V transposed: [H_kv][D][page_size]
+  }
+}
+
+// V cache write of all rows of one (sequence, kv head).  V is kept transposed, [H_kv][D][page_size], so the values of
+// one row are 128 bytes apart; eight neighbouring lanes take eight rows of the same d, which fall into the same
+// 128-byte line (one write transaction instead of eight).
+__global__ __launch_bounds__(256) void k_v_write_bf16(const bf16_t *qkv, int Hq, const int32_t *cu, RowIndex ri, SlotState st, KvLayer kv) {
+  const int b = blockIdx.x, hk = blockIdx.y;
+  const int r0 = cu[b], nr = cu[b + 1] - r0;
+  if (nr <= 0) return;
+  const int D = kv.head_dim, Hkv = kv.n_kv_heads, P = kv.page_size, stride = (Hq + 2 * Hkv) * D;
+  const int slot = slot_of(ri.seq_slot, b, st);
+  const int L = st.prefix_len[slot];
+  const int32_t *pt = st.page_table + (size_t)slot * st.table_stride;
+  for (int rb = 0; rb < nr; rb += 8) {
+    const int r = rb + (threadIdx.x & 7);
+    if (r >= nr) continue;
+    const int pos = L + ri.row_map[r0 + r] % ri.B;
+    bf16_t *vc = (bf16_t *)kv.base + (size_t)pt[pos / P] * 2 * Hkv * P * D + (size_t)Hkv * P * D + (size_t)hk * D * P + pos % P;
+    const bf16_t *v = qkv + (size_t)(r0 + r) * stride + (size_t)(Hq + Hkv + hk) * D;
+    for (int d = threadIdx.x >> 3; d < D; d += 32) vc[(size_t)d * P] = v[d];
+  }
 }
 
 void rope_kv_write(hipStream_t s, int dtype, void *qkv, int n_q_heads, Rows rows, RowIndex ri, SlotState st,
-                   KvLayer kv, const float2 *rope_table) {
+                   KvLayer kv, const float2 *rope_table, int n_seq, const int32_t *cu) {
   if (rows.cap <= 0) return;
   if (dtype == FOCUS_BF16 && kv.head_dim % 16 == 0 && (((uintptr_t)qkv | (uintptr_t)kv.base) & 15) == 0) {
-    k_rope_kv_write_bf16<<<rows.cap, 256, 0, s>>>((bf16_t *)qkv, n_q_heads, rows, ri, st, kv, rope_table);
+    const bool by_seq = cu != nullptr && n_seq > 0;      // the V scatter per (sequence, kv head) when the row ranges are known
+    k_rope_kv_write_bf16<<<rows.cap, 256, 0, s>>>((bf16_t *)qkv, n_q_heads, rows, ri, st, kv, rope_table, by_seq ? 0 : 1);
+    if (by_seq) k_v_write_bf16<<<dim3(n_seq, kv.n_kv_heads), 256, 0, s>>>((const bf16_t *)qkv, n_q_heads, cu, ri, st, kv);
     return;
   }
   if (dtype == FOCUS_F32)
