@@ -151,6 +151,8 @@ class Workload:
     constraints: int = 0        # bit0 AR-context, bit1 placeholder integrity
     conf_threshold: float = 0.9
     intra_block_cache: int = 0  # 1 = delayed intra-block K/V cache with the neighbour-aware stability criterion
+    selection: int = 0          # 0 TOP, 1 RANDOM, 2 BOTTOM pick of the K candidates
+    selection_seed: int = 0
     steps: int = 1
     shuffle_pages: bool = False
     extra_blocks: int = 0       # further blocks each sequence will generate (pages and positions are planned for them)

@@ -48,6 +48,7 @@ enum { FOCUS_OK = 0, FOCUS_EINVAL = -1, FOCUS_ENOMEM = -2, FOCUS_EHIP = -3 };
 enum { FOCUS_F32 = 0, FOCUS_BF16 = 1 };
 enum { FOCUS_BUDGET_TOPK = 0, FOCUS_BUDGET_RATIO = 1, FOCUS_BUDGET_DYNAMIC = 2, FOCUS_BUDGET_OVERRIDE = 3 };
 enum { FOCUS_KEEP_AR_CONTEXT = 1, FOCUS_KEEP_PLACEHOLDERS = 2 };
+enum { FOCUS_SELECT_TOP = 0, FOCUS_SELECT_RANDOM = 1, FOCUS_SELECT_BOTTOM = 2 };
 
 typedef struct focus_ctx focus_ctx;
 
@@ -77,6 +78,12 @@ typedef struct focus_config {
                                App. E.3.1): a position whose token and right neighbour were decoded before a step it
                                took part in keeps that step's K/V in every layer from then on and leaves the rows of
                                all later steps of the block; decoded positions not yet frozen are always retained */
+  int32_t selection;        /* FOCUS_SELECT_*: which min(K, |M|) masked positions the budget picks.  TOP is the method
+                               (largest delta).  BOTTOM (smallest delta) and RANDOM are the controls of the selection
+                               validation (Sec. 5.2); ties go to the lower position, the structural constraints apply
+                               to the pick unchanged */
+  uint32_t selection_seed;  /* RANDOM: position j of slot s is ranked by output number c + 1 of the SplitMix64 generator
+                               started at selection_seed, c = (s * 2^32 + total_steps of the slot before the step) * 64 + j */
 } focus_config;
 
 /* Device pointers.  The per-layer members are HOST arrays of n_layers device pointers. */

@@ -71,6 +71,8 @@ class OracleConfig:
     conf_threshold: float = 0.9
     placeholder_unprocessed_only: bool = False   # alternative reading of placeholder integrity
     intra_block_cache: int = 0    # 1: delayed intra-block K/V cache with the neighbour-aware stability criterion (Sec. 4.3)
+    selection: int = 0            # which K masked positions are picked: 0 TOP (the method), 1 RANDOM, 2 BOTTOM (Sec. 5.2)
+    selection_seed: int = 0       # RANDOM: seed of the counter-based generator
 
 
 @dataclass
@@ -84,11 +86,12 @@ class SeqState:
     cached: Optional[List[bool]] = None    # C: position's K/V is frozen in every layer (Sec. 4.3); None = none
     token_sum: int = 0                     # running sum of tokens decoded per step
     total_steps: int = 0                   # number of steps this sequence took part in
+    slot: int = 0                          # the scheduler's slot of the sequence (names its random stream)
 
 
-def new_seq_state(cfg: OracleConfig, prefix_len: int, pages: Sequence[int]) -> SeqState:
+def new_seq_state(cfg: OracleConfig, prefix_len: int, pages: Sequence[int], slot: int = 0) -> SeqState:
     B = cfg.block_size
-    return SeqState(prefix_len, list(pages), [cfg.mask_token_id] * B, [True] * B, [False] * B, [False] * B)
+    return SeqState(prefix_len, list(pages), [cfg.mask_token_id] * B, [True] * B, [False] * B, [False] * B, slot=slot)
 
 
 class Weights:
@@ -256,15 +259,34 @@ def budget(cfg: OracleConfig, dI: Sequence[float], masked: Sequence[bool], token
 # ---------------------------------------------------------------------------------------------
 # Alg. 1 phase 3: selection
 
+_MASK64 = (1 << 64) - 1
+
+
+def selection_key(seed: int, slot: int, step: int, j: int) -> int:
+    """64-bit random key of block position j for the RANDOM strategy: output number c + 1 of the SplitMix64
+    generator (Steele, Lea, Flood 2014) started at `seed`, with the counter c = (slot * 2^32 + step) * 64 + j,
+    step = the sequence's total_steps before this step.  Reading: the paper only says K candidates are drawn at
+    random; a counter-based stream keeps the draw a pure function of (seed, slot, step, position)."""
+    c = ((((slot << 32) + step) << 6) + j) & _MASK64
+    z = (seed + (c + 1) * 0x9E3779B97F4A7C15) & _MASK64
+    z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & _MASK64
+    z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & _MASK64
+    return z ^ (z >> 31)
+
+
 def select(cfg: OracleConfig, dI: Sequence[float], masked: Sequence[bool], processed: Sequence[bool],
-           K: int, cached: Optional[Sequence[bool]] = None) -> List[int]:
+           K: int, cached: Optional[Sequence[bool]] = None, rand_keys: Optional[Sequence[int]] = None) -> List[int]:
     """The retained set S of one sequence, ascending.
 
     K >= B keeps the whole block (no eviction: the step is the dense block decode).  Otherwise the
     min(K, |M|) masked positions with the largest delta are taken (ties: lower index first; NaN
     ranks below every number), then, per Alg. 1: predecessors i-1 of those picks (bit0), then every
     masked j below max(S) (bit1).  The predecessor of position 0 lies in the prefix; predecessors are
-    added once, for the top-K picks only."""
+    added once, for the top-K picks only.
+
+    cfg.selection swaps the pick for the validation of Sec. 5.2: BOTTOM takes the min(K, |M|) masked positions
+    with the smallest delta (ties: lower index first; NaN still ranks last), RANDOM the ones with the largest
+    rand_keys (ties: lower index first).  Everything after the pick is unchanged."""
     B = cfg.block_size
     cached = [False] * B if cached is None else cached
     uncached = [j for j in range(B) if not cached[j]]
@@ -278,7 +300,11 @@ def select(cfg: OracleConfig, dI: Sequence[float], masked: Sequence[bool], proce
         return owed
 
     def key(j):
+        if cfg.selection == 1:
+            return (-int(rand_keys[j]), j)
         v = float(dI[j])
+        if cfg.selection == 2:
+            return ((v if v == v else -NEG_INF), j)
         return (-(v if v == v else NEG_INF), j)
     top = sorted(cand, key=key)[:min(K, len(cand))]
     S = set(top)
@@ -477,7 +503,9 @@ def focus_step(cfg: OracleConfig, W: Weights, pool: KVPool, seqs: List[SeqState]
             K = budget(cfg, tr.delta_I[b], st.masked, st.token_sum, st.total_steps,
                        None if k_override is None else k_override[b])
             tr.K.append(K)
-            S = select(cfg, tr.delta_I[b], st.masked, st.processed, K, st.cached)
+            rk = [selection_key(cfg.selection_seed, st.slot, st.total_steps, j) for j in range(B)] \
+                if cfg.selection == 1 else None
+            S = select(cfg, tr.delta_I[b], st.masked, st.processed, K, st.cached, rk)
         tr.keep.append(S)
         for p in S:
             st.processed[p] = True

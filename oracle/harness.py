@@ -20,7 +20,8 @@ def oracle_config(wl: Workload, **over) -> fo.OracleConfig:
         mask_token_id=wl.mask_token_id, page_size=wl.page_size, rms_eps=wl.rms_eps, rope_base=wl.rope_base,
         evict_layer=wl.evict_layer, importance_mode=wl.importance_mode, maxpool_k=wl.maxpool_k,
         budget_mode=wl.budget_mode, topk=wl.topk, keep_ratio=wl.keep_ratio, alpha=wl.alpha,
-        constraints=wl.constraints, conf_threshold=wl.conf_threshold, intra_block_cache=wl.intra_block_cache)
+        constraints=wl.constraints, conf_threshold=wl.conf_threshold, intra_block_cache=wl.intra_block_cache,
+        selection=wl.selection, selection_seed=wl.selection_seed)
     for k, v in over.items():
         setattr(cfg, k, v)
     return cfg
@@ -74,7 +75,7 @@ def oracle_batch(wl: Workload, seq_ids: Optional[Sequence[int]] = None, lazy_emb
     tables, n_pages = wl.page_tables(lens)
     ids = list(range(wl.batch)) if seq_ids is None else list(seq_ids)
     pool = fo.KVPool(cfg)
-    states = [fo.new_seq_state(cfg, lens[b], tables[b]) for b in ids]
+    states = [fo.new_seq_state(cfg, lens[b], tables[b], slot=i) for i, b in enumerate(ids)]
     if wl.prefill == "synthetic":
         for l in range(wl.n_layers):
             for b in ids:

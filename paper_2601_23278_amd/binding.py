@@ -30,7 +30,8 @@ class focus_config(C.Structure):
                                          "n_pages", "evict_layer", "importance_mode", "maxpool_k", "budget_mode",
                                          "topk")] + \
                [("keep_ratio", C.c_float), ("alpha", C.c_float), ("constraints", C.c_int32),
-                ("conf_threshold", C.c_float), ("intra_block_cache", C.c_int32)]
+                ("conf_threshold", C.c_float), ("intra_block_cache", C.c_int32), ("selection", C.c_int32),
+                ("selection_seed", C.c_uint32)]
 
 
 class focus_weights(C.Structure):

@@ -104,6 +104,7 @@ const char *check_config(const focus_config &c) {
   if (c.budget_mode < 0 || c.budget_mode > 3) return "unknown budget_mode";
   if (c.constraints & ~3) return "unknown constraint bits";
   if (c.intra_block_cache != 0 && c.intra_block_cache != 1) return "intra_block_cache must be 0 or 1";
+  if (c.selection < FOCUS_SELECT_TOP || c.selection > FOCUS_SELECT_BOTTOM) return "selection must be a FOCUS_SELECT_* value";
   if (!(c.rms_eps > 0.f) || !(c.rope_base > 1.f)) return "rms_eps must be > 0 and rope_base > 1";
   return nullptr;
 }
@@ -558,6 +559,7 @@ int focus_step(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32_t *s
     a.importance_mode = g.importance_mode; a.budget_mode = g.budget_mode; a.K_fixed = fixed_budget(g);
     a.constraints = g.constraints; a.alpha = g.alpha; a.k_override = k_override; a.keep_override = keep_override;
     a.seq_slot = seq_slot; a.st = st; a.update_state = 1; a.intra_block_cache = g.intra_block_cache;
+    a.selection = g.selection; a.selection_seed = g.selection_seed;
     a.imp_prev_out = o.importance_prev; a.imp_out = o.importance;
     a.delta_out = o.delta_I ? o.delta_I : ctx->at<float>(pl.off_delta);
     a.K_out = o.K ? o.K : ctx->at<int32_t>(pl.off_K);
@@ -608,6 +610,7 @@ int focus_select_compact(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const 
   a.importance_mode = g.importance_mode; a.budget_mode = g.budget_mode; a.K_fixed = fixed_budget(g);
   a.constraints = g.constraints; a.alpha = g.alpha; a.k_override = k_override; a.keep_override = nullptr;
   a.seq_slot = seq_slot; a.st = ctx->slots(); a.update_state = 0; a.intra_block_cache = g.intra_block_cache;
+  a.selection = g.selection; a.selection_seed = g.selection_seed;
   a.delta_out = nullptr; a.K_out = out->K; a.keep_out = out->keep_bits;
   a.n_keep_out = ctx->at<int32_t>(ctx->plan.off_n_keep); a.vis_out = nullptr;
   fk::select(s, a);

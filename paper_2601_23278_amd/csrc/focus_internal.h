@@ -131,6 +131,8 @@ struct SelectArgs {
   const int32_t *seq_slot;
   SlotState st;
   int intra_block_cache;                       // Sec. 4.3: frozen positions are never retained, decoded unfrozen ones always
+  int selection;                               // FOCUS_SELECT_*: pick by largest delta, by a random key, by smallest delta
+  uint32_t selection_seed;
   int update_state;                            // processed_bits |= keep
   float *imp_prev_out, *imp_out, *delta_out;   // [n, B] or null
   int32_t *K_out;

@@ -85,12 +85,28 @@ __global__ __launch_bounds__(64) void k_select(SelectArgs a) {
       keep = all & ~frozen;                      // no eviction: the whole block (what is left of it) stays
     } else {
       // rank of position j among the masked positions: number that order before it
-      float v = (d != d) ? -INFINITY : d;        // NaN ranks last
       int rank = 0;
-      for (int i = 0; i < B; ++i) {
-        float vi = __shfl(v, i);
-        bool mi = (masked >> i) & 1ull;
-        rank += (mi && (vi > v || (vi == v && i < j))) ? 1 : 0;
+      if (a.selection == FOCUS_SELECT_RANDOM) {
+        // control of Sec. 5.2: SplitMix64 output number c + 1 from the seed, c = (slot * 2^32 + step) * 64 + j
+        const uint64_t c = ((((uint64_t)slot << 32) + (uint64_t)(uint32_t)a.st.total_steps[slot]) << 6) + (uint64_t)j;
+        uint64_t z = (uint64_t)a.selection_seed + (c + 1) * 0x9E3779B97F4A7C15ull;
+        z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+        z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+        z ^= z >> 31;
+        const unsigned lo = (unsigned)z, hi = (unsigned)(z >> 32);
+        for (int i = 0; i < B; ++i) {
+          const uint64_t zi = ((uint64_t)__shfl(hi, i) << 32) | __shfl(lo, i);
+          const bool mi = (masked >> i) & 1ull;
+          rank += (mi && (zi > z || (zi == z && i < j))) ? 1 : 0;
+        }
+      } else {
+        float v = (a.selection == FOCUS_SELECT_BOTTOM) ? -d : d;   // BOTTOM: smallest delta first
+        v = (v != v) ? -INFINITY : v;                              // NaN ranks last
+        for (int i = 0; i < B; ++i) {
+          float vi = __shfl(v, i);
+          bool mi = (masked >> i) & 1ull;
+          rank += (mi && (vi > v || (vi == v && i < j))) ? 1 : 0;
+        }
       }
       const uint64_t top = __ballot(in && is_masked && rank < K);
       keep = top;

@@ -23,6 +23,7 @@ def config_from_workload(wl: Workload, max_batch: int, max_prefix_len: int, n_pa
     c.budget_mode, c.topk, c.keep_ratio, c.alpha = wl.budget_mode, wl.topk, wl.keep_ratio, wl.alpha
     c.constraints, c.conf_threshold = wl.constraints, wl.conf_threshold
     c.intra_block_cache = wl.intra_block_cache
+    c.selection, c.selection_seed = wl.selection, wl.selection_seed
     return c
 
 

@@ -214,6 +214,14 @@ def test_c1_variants_fp32_exact(variant):
     compare_steps(wl, wl.steps, 1e-3, exact=True, k_override=ko)
 
 
+@pytest.mark.parametrize("selection,topk", [(1, 2), (1, 4), (2, 2), (2, 8)])
+def test_c1_random_and_bottom_selection_fp32_exact(selection, topk):
+    """Controls of the selection validation (Sec. 5.2): fixed K, the pick replaced by Random / Bottom."""
+    wl = fi.workload("c1_tiny", budget_mode=0, topk=topk, selection=selection, selection_seed=20260123, steps=4,
+                     constraints=1 if topk == 4 else 0)
+    compare_steps(wl, wl.steps, 1e-3, exact=True)
+
+
 def test_c1_intra_block_cache_fp32_exact():
     """Delayed intra-block K/V cache with the neighbour-aware stability criterion (Sec. 4.3): a low threshold makes
     several tokens commit per step, so positions freeze, leave the rows of the early layers and keep their K/V."""
@@ -260,12 +268,13 @@ def install_states(pk, sess, wl, masks, sums, steps):
         sess.focus.focus_set_state(b, s)
 
 
-@pytest.mark.parametrize("mode,constraints", [(0, 0), (1, 0), (2, 0), (2, 3), (3, 1), (1, 2)])
-def test_select_compact_stage_bit_exact(mode, constraints):
+@pytest.mark.parametrize("mode,constraints,selection", [(0, 0, 0), (1, 0, 0), (2, 0, 0), (2, 3, 0), (3, 1, 0), (1, 2, 0),
+                                                        (0, 0, 1), (3, 3, 1), (0, 0, 2), (2, 3, 2)])
+def test_select_compact_stage_bit_exact(mode, constraints, selection):
     pk, runner = _pk()
     B, n = 32, 37
     wl = fi.workload("c1_tiny", block_size=B, batch=n, budget_mode=mode, topk=3, keep_ratio=0.2, constraints=constraints,
-                     prefill="synthetic", n_layers=2)
+                     prefill="synthetic", n_layers=2, selection=selection, selection_seed=0xC0FFEE)
     sess = runner.open_session(wl, DEV)
     cfg = oracle_config(wl)
     r = np.random.default_rng(100 + mode * 10 + constraints)
@@ -291,7 +300,8 @@ def test_select_compact_stage_bit_exact(mode, constraints):
             masked = [bool((masks[b] >> p) & 1) for p in range(B)]
             K = fo.budget(cfg, dI[b].astype(np.float64), masked, sums[b], stp[b], ko[b])
             assert int(g["K"][b]) == K, (trial, b)
-            S = fo.select(cfg, dI[b].astype(np.float64), masked, [False] * B, K)
+            rk = [fo.selection_key(cfg.selection_seed, b, stp[b], j) for j in range(B)]
+            S = fo.select(cfg, dI[b].astype(np.float64), masked, [False] * B, K, None, rk)
             assert positions_of(u64(g["keep_bits"][b]), B) == S, (trial, b)
             keep.append(S)
         cu, rm = fo.compact(keep, B)

@@ -293,6 +293,85 @@ def test_select_hand_cases():
     assert len(fo.select(tiny_cfg(block_size=B), dI, [False] * 7 + [True], [False] * B, 1)) == 1
 
 
+# ---------------------------------------------------------------------------------------------
+# Sec. 5.2: Top / Random / Bottom pick of the K candidates
+
+def test_selection_key_is_the_published_splitmix64_stream():
+    # first outputs of SplitMix64 started at 0 (test vector circulated with the generator's reference code)
+    want = [0xE220A8397B1DCDAF, 0x6E789E6AA1B965F4, 0x06C45D188009454F]
+    assert [fo.selection_key(0, 0, 0, j) for j in range(3)] == want
+    # the counter is (slot * 2^32 + step) * 64 + j: a step moves 64 outputs ahead, a slot 2^38
+    assert fo.selection_key(0, 0, 1, 0) != fo.selection_key(0, 0, 0, 0)
+    state, outs = 0, []
+    for _ in range(64 + 3):
+        state = (state + 0x9E3779B97F4A7C15) & (2 ** 64 - 1)
+        z = state
+        z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & (2 ** 64 - 1)
+        z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & (2 ** 64 - 1)
+        outs.append(z ^ (z >> 31))
+    assert [fo.selection_key(0, 0, 1, j) for j in range(3)] == outs[64:67]
+    # a different seed is a different start of the same stream
+    assert fo.selection_key(0x9E3779B97F4A7C15, 0, 0, 0) == outs[1]
+
+
+@pytest.mark.parametrize("constraints", [0, 3])
+def test_bottom_pick_is_the_top_pick_of_the_negated_delta(constraints):
+    r = np.random.default_rng(31 + constraints)
+    B = 8
+    top, bot = tiny_cfg(block_size=B, constraints=constraints), tiny_cfg(block_size=B, constraints=constraints, selection=2)
+    for trial in range(300):
+        dI = list(np.round(r.normal(size=B), 1))
+        masked = list(r.random(B) < 0.7)
+        for K in range(0, B + 1):
+            neg = [-x + 0.0 for x in dI]
+            assert fo.select(bot, dI, masked, [False] * B, K) == select_brute(neg, masked, K, B, constraints)
+            assert fo.select(bot, dI, masked, [False] * B, K) == fo.select(top, neg, masked, [False] * B, K)
+    nan = float("nan")
+    allm = [True] * B
+    assert fo.select(tiny_cfg(block_size=B, selection=2), [nan, 0.0, nan, -1.0] + [2.0] * 4, allm, [False] * B, 2) == [1, 3]
+    assert fo.select(tiny_cfg(block_size=B, selection=2), [0.5, 0.1, 0.1, 0.9, 0.1, 3, 3, 3], allm, [False] * B, 2) == [1, 2]
+
+
+def test_random_pick_is_a_uniform_k_subset_of_the_masked_positions():
+    B, K = 8, 3
+    cfg = tiny_cfg(block_size=B, selection=1, selection_seed=7)
+    masked = [True, True, False, True, True, True, False, True]
+    M = [j for j in range(B) if masked[j]]
+    dI = [float(j) for j in range(B)]                          # the delta must play no part
+    counts = np.zeros(B)
+    n = 6000
+    for step in range(n):
+        rk = [fo.selection_key(cfg.selection_seed, 5, step, j) for j in range(B)]
+        S = fo.select(cfg, dI, masked, [False] * B, K, None, rk)
+        assert len(S) == K and set(S) <= set(M)
+        assert S == sorted(sorted(M, key=lambda j: (-rk[j], j))[:K])
+        counts[S] += 1
+    # every masked position is picked with probability K / |M| = 1/2: binomial std 0.0065, allow 5 sigma
+    assert np.all(np.abs(counts[M] / n - K / len(M)) < 0.033) and counts[2] == counts[6] == 0
+    # K beyond the candidates keeps them all, like the other strategies
+    rk = [fo.selection_key(7, 0, 0, j) for j in range(B)]
+    for sel in (0, 1, 2):
+        assert fo.select(tiny_cfg(block_size=B, selection=sel), dI, masked, [False] * B, 7, None, rk) == M
+    # ties in the key go to the lower position
+    assert fo.select(cfg, dI, [True] * B, [False] * B, 2, None, [5, 9, 9, 1, 9, 0, 0, 0]) == [1, 2]
+
+
+def test_random_pick_inside_a_step_uses_slot_and_step_counters():
+    cfg = tiny_cfg(selection=1, selection_seed=3, keep_ratio=0.25)
+    W = tiny_weights(cfg)
+    pool, seqs, _ = tiny_batch(cfg, W, [6, 9])
+    seqs[0].slot, seqs[1].slot = 4, 2
+    B = cfg.block_size
+    for step in range(3):
+        before = [(list(st.masked), st.total_steps) for st in seqs]
+        tr = fo.focus_step(cfg, W, pool, seqs)
+        for b, st in enumerate(seqs):
+            masked, steps = before[b]
+            M = [j for j in range(B) if masked[j]]
+            rk = [fo.selection_key(3, st.slot, steps, j) for j in range(B)]
+            assert tr.keep[b] == sorted(sorted(M, key=lambda j: (-rk[j], j))[:min(tr.K[b], len(M))])
+
+
 def test_compact_order_and_permutation_invariance():
     keep = [[1, 5], [], [0, 2, 7], [3]]
     cu, rm = fo.compact(keep, 8)
