@@ -15,8 +15,11 @@ What follows the paper directly (each function cites its passage):
   * reduced forward of the remaining layers          -> focus_step()
   * confidence decoding and the running mean of
     decoded tokens, Alg. 1 last lines, App. E.3.1    -> confidence(), commit()
+  * Top / Random / Bottom pick of the candidates,
+    Sec. 5.2                                         -> select(), selection_key()
 The transformer layer itself (RMSNorm, rotate-half RoPE, grouped-query attention over an exact
-prefix KV cache that is bidirectional inside the block, SwiGLU) is the textbook definition.
+prefix KV cache that is bidirectional inside the block, SwiGLU) is the textbook definition, and so
+is the mixture-of-experts feed-forward of the paper's second model (Sec. 5.1): route(), moe_ffn().
 
 Readings taken where the paper is silent are listed next to the code that takes them.
 
@@ -29,7 +32,10 @@ Parity pins (tests/test_oracle_*.py): softmax rows sum to one; sum of importance
 B * H_q and the delta sums to zero; importance with pooling off equals a column sum of the
 block-local softmax; brute-force set algebra for select(); identity of keep-all with an
 independently written dense block decode; permutation invariance of compaction; page-placement
-invariance; Eq. 4 hand values (alpha 1.5, mean 1 gives K 2); the running-mean recurrences.
+invariance; Eq. 4 hand values (alpha 1.5, mean 1 gives K 2); the running-mean recurrences; the
+random pick's generator against SplitMix64's published outputs and a frequency test; the
+mixture-of-experts layer against a masked dense formulation built on torch.topk, hand-worked routes,
+and the dense model when all experts share one set of weights.
 Whether the delta predicts decodability on trained weights is parity unpinned (no weights here).
 """
 from __future__ import annotations
@@ -73,6 +79,13 @@ class OracleConfig:
     intra_block_cache: int = 0    # 1: delayed intra-block K/V cache with the neighbour-aware stability criterion (Sec. 4.3)
     selection: int = 0            # which K masked positions are picked: 0 TOP (the method), 1 RANDOM, 2 BOTTOM (Sec. 5.2)
     selection_seed: int = 0       # RANDOM: seed of the counter-based generator
+    # mixture-of-experts feed-forward (the paper's second model, Sec. 5.1, is an MoE; it gives no formulas, see moe_ffn)
+    n_experts: int = 0            # E; 0 = every layer has the dense SwiGLU feed-forward
+    experts_per_token: int = 0    # k
+    expert_ffn: int = 0           # F_e, inner width of a routed expert
+    shared_ffn: int = 0           # F_s, inner width of the always-on shared expert; 0 = none
+    first_moe_layer: int = 0      # layers below it keep the dense feed-forward
+    route_scale: float = 1.0      # factor on the routed experts' sum
 
 
 @dataclass
@@ -391,12 +404,64 @@ def _project_qkv(cfg: OracleConfig, w: Dict[str, np.ndarray], X: np.ndarray, abs
     return rope(q, abs_pos, cfg.rope_base), rope(k, abs_pos, cfg.rope_base), v
 
 
-def _finish_layer(cfg: OracleConfig, w: Dict[str, np.ndarray], X: np.ndarray, attn: np.ndarray) -> np.ndarray:
+def swiglu(u: np.ndarray, w_gate_up: np.ndarray, w_down: np.ndarray) -> np.ndarray:
+    """SwiGLU feed-forward: (silu(u Wg^T) * (u Wu^T)) Wd^T with w_gate_up = [Wg; Wu] stacked by rows."""
+    F = w_gate_up.shape[0] // 2
+    gu = u @ w_gate_up.T
+    return (silu(gu[:, :F]) * gu[:, F:]) @ w_down.T
+
+
+def route(cfg: OracleConfig, logits: np.ndarray, forced: Optional[Sequence[int]] = None):
+    """Experts and mixing weights of one row from its router logits [E].
+
+    The k experts with the largest router probability p = softmax(logits), taken in descending order (ties: lower
+    expert first; the decision is made on the logits, which order the same way), or the `forced` list in its own
+    order (teacher forcing).  Weights: p over the chosen experts, renormalised to sum to one, times route_scale."""
+    E = logits.shape[0]
+    p = softmax_rows(logits[None, :])[0]
+    chosen = list(forced) if forced is not None else \
+        sorted(range(E), key=lambda i: (-float(logits[i]), i))[:cfg.experts_per_token]
+    tot = sum(float(p[i]) for i in chosen)
+    return chosen, [float(np.float32(cfg.route_scale)) * float(p[i]) / tot for i in chosen]
+
+
+def moe_ffn(cfg: OracleConfig, w: Dict[str, np.ndarray], u: np.ndarray, forced=None):
+    """Mixture-of-experts feed-forward on normalised rows u [r, h].
+
+    Reading (the paper evaluates an MoE diffusion model, Sec. 5.1, without stating its layer): the common
+    token-choice layer.  A linear router scores E experts per row, route() picks k of them with weights, each
+    expert is a SwiGLU feed-forward of inner width F_e, the row's output is the weighted sum of its experts'
+    outputs plus, when F_s > 0, a shared SwiGLU expert that every row goes through.
+    forced[i]: expert list to use for row i instead of the router's pick.  Returns (y, experts, weights)."""
+    r = u.shape[0]
+    logits = u @ w["w_router"].T
+    y = np.zeros((r, cfg.hidden))
+    experts, weights = [], []
+    for i in range(r):
+        ch, wt = route(cfg, logits[i], None if forced is None else forced[i])
+        experts.append(ch)
+        weights.append(wt)
+        for e, g in zip(ch, wt):
+            y[i] += g * swiglu(u[i:i + 1], w["w_expert_gate_up"][e], w["w_expert_down"][e])[0]
+    if cfg.shared_ffn > 0:
+        y += swiglu(u, w["w_shared_gate_up"], w["w_shared_down"])
+    return y, experts, weights
+
+
+def _finish_layer(cfg: OracleConfig, w: Dict[str, np.ndarray], X: np.ndarray, attn: np.ndarray,
+                  layer: int = 0, row_ids: Optional[Sequence[int]] = None, route_override=None, route_log=None) -> np.ndarray:
+    """Output projection, residual, then the feed-forward (dense, or mixture-of-experts from first_moe_layer on) and its
+    residual.  row_ids[i] = b * B + p names row i for route_override[layer][row id] and for route_log[layer]."""
     X = X + attn.reshape(X.shape[0], cfg.n_q_heads * cfg.head_dim) @ w["w_o"].T      # explicit width: a step may have no rows
     u = rmsnorm(X, w["mlp_norm"], cfg.rms_eps)
-    gu = u @ w["w_gate_up"].T
-    act = silu(gu[:, :cfg.ffn]) * gu[:, cfg.ffn:]
-    return X + act @ w["w_down"].T
+    if cfg.n_experts > 0 and layer >= cfg.first_moe_layer:
+        forced = None if route_override is None else [route_override[layer][rid] for rid in row_ids]
+        y, experts, weights = moe_ffn(cfg, w, u, forced)
+        if route_log is not None:
+            for i, rid in enumerate(row_ids):
+                route_log.setdefault(layer, {})[rid] = (experts[i], weights[i])
+        return X + y
+    return X + swiglu(u, w["w_gate_up"], w["w_down"])
 
 
 @dataclass
@@ -418,12 +483,13 @@ class StepTrace:
     argmax: Optional[np.ndarray] = None
     committed: List[List[int]] = field(default_factory=list)  # per sequence, positions unmasked this step
     n_decoded: List[int] = field(default_factory=list)
+    route: Dict[int, Dict[int, tuple]] = field(default_factory=dict)   # MoE layer -> row id b * B + p -> (experts, weights)
 
 
 def focus_step(cfg: OracleConfig, W: Weights, pool: KVPool, seqs: List[SeqState],
                k_override: Optional[Sequence[int]] = None,
                keep_override: Optional[Sequence[Sequence[int]]] = None,
-               score_cast=None, conf_cast=None, record_layers=None) -> StepTrace:
+               score_cast=None, conf_cast=None, record_layers=None, route_override=None) -> StepTrace:
     """One FOCUS inference step (Alg. 1) for a batch of sequences, in place on `seqs` and `pool`.
 
     Order of work, as in Alg. 1 and App. C: layers below the eviction layer e run on the whole
@@ -438,7 +504,9 @@ def focus_step(cfg: OracleConfig, W: Weights, pool: KVPool, seqs: List[SeqState]
     keep_override: per-sequence retained sets to use instead of budget()+select() (teacher forcing).
     score_cast / conf_cast: optional functions applied to the delta and to the confidences before
     the integer decisions (e.g. rounding to float32 so both sides decide in the same precision).
-    record_layers: layers (> e) whose incoming residual stream is kept in the trace."""
+    record_layers: layers (> e) whose incoming residual stream is kept in the trace.
+    route_override: mixture-of-experts layers only: route_override[l][b * B + p] = the experts row (b, p) uses in layer l
+    instead of the router's pick (teacher forcing); the trace's `route` records what every row used."""
     B, e = cfg.block_size, cfg.evict_layer
     n = len(seqs)
     tr = StepTrace()
@@ -461,6 +529,7 @@ def focus_step(cfg: OracleConfig, W: Weights, pool: KVPool, seqs: List[SeqState]
     X = np.concatenate([W.embed[np.array(row, dtype=np.int64)].reshape(len(row), cfg.hidden) for row in ids], axis=0) \
         if n else np.zeros((0, cfg.hidden))
     abs_pos = np.array([st.prefix_len + p for b, st in enumerate(seqs) for p in U[b]], dtype=np.int64)
+    full_ids = [b * B + p for b in range(n) for p in U[b]]
 
     def block_keys(l, st):
         Kc, _ = pool.read(l, st.pages, [st.prefix_len + p for p in range(B)])
@@ -479,7 +548,7 @@ def focus_step(cfg: OracleConfig, W: Weights, pool: KVPool, seqs: List[SeqState]
                 tr.I_prev.append(importance(q[sl], block_keys(l, st), cfg.maxpool_k))
             Kc, Vc = pool.read(l, st.pages, list(range(st.prefix_len + B)))
             attn[sl] = _attention(cfg, q[sl], Kc, Vc)
-        X = _finish_layer(cfg, w, X, attn)
+        X = _finish_layer(cfg, w, X, attn, l, full_ids, route_override, tr.route)
     tr.hidden_full = X.copy()
 
     # layer e: projections and K/V fill for those rows, importance, delta
@@ -520,7 +589,7 @@ def focus_step(cfg: OracleConfig, W: Weights, pool: KVPool, seqs: List[SeqState]
         if sl.stop > sl.start:
             Kc, Vc = pool.read(e, st.pages, list(range(st.prefix_len + B)))
             attn[sl] = _attention(cfg, qp[sl], Kc, Vc)
-    Xp = _finish_layer(cfg, w, Xp, attn)
+    Xp = _finish_layer(cfg, w, Xp, attn, e, tr.row_map, route_override, tr.route)
 
     # layers e+1 .. on the retained rows
     for l in range(e + 1, cfg.n_layers):
@@ -539,7 +608,7 @@ def focus_step(cfg: OracleConfig, W: Weights, pool: KVPool, seqs: List[SeqState]
             vis = list(range(st.prefix_len)) + [st.prefix_len + p for p in range(B) if st.processed[p]]
             Kc, Vc = pool.read(l, st.pages, vis)
             attn[sl] = _attention(cfg, q[sl], Kc, Vc)
-        Xp = _finish_layer(cfg, w, Xp, attn)
+        Xp = _finish_layer(cfg, w, Xp, attn, l, tr.row_map, route_override, tr.route)
     tr.hidden_packed = Xp
 
     # decode and verify
@@ -583,7 +652,7 @@ def prefill(cfg: OracleConfig, W: Weights, pool: KVPool, seqs: List[SeqState], p
                 for i in range(len(blk)):
                     pool.write(l, st.pages, c0 + i, k[i], v[i])
                 Kc, Vc = pool.read(l, st.pages, list(range(c0 + len(blk))))
-                X = _finish_layer(cfg, w, X, _attention(cfg, q, Kc, Vc))
+                X = _finish_layer(cfg, w, X, _attention(cfg, q, Kc, Vc), l)
 
 
 def finalize_blocks(cfg: OracleConfig, W: Weights, pool: KVPool, seqs: List[SeqState]) -> List[bool]:
@@ -610,7 +679,7 @@ def finalize_blocks(cfg: OracleConfig, W: Weights, pool: KVPool, seqs: List[SeqS
             for i, p in enumerate(rows_p):
                 pool.write(l, st.pages, st.prefix_len + p, k[i], v[i])
             Kc, Vc = pool.read(l, st.pages, list(range(st.prefix_len + B)))
-            X = _finish_layer(cfg, w, X, _attention(cfg, q, Kc, Vc))
+            X = _finish_layer(cfg, w, X, _attention(cfg, q, Kc, Vc), l)
         st.prefix_len += B
         st.tokens = [cfg.mask_token_id] * B
         st.masked = [True] * B

@@ -796,3 +796,111 @@ def test_intra_block_cache_off_or_idle_changes_nothing():
             pool, states, _ = tiny_batch(cfg, W, [8, 12], seed=12)
             outs.append(fo.focus_step(cfg, W, pool, states))
         assert outs[0].keep == outs[1].keep and np.array_equal(outs[0].logits, outs[1].logits)
+
+
+# ---------------------------------------------------------------------------------------------
+# mixture-of-experts feed-forward (second model of Sec. 5.1; the layer is the common token-choice one)
+
+def torch_swiglu(u, w_gate_up, w_down):
+    F_ = w_gate_up.shape[0] // 2
+    u, wg, wu, wd = (torch.from_numpy(np.asarray(a)) for a in (u, w_gate_up[:F_], w_gate_up[F_:], w_down))
+    return ((F.silu(u @ wg.T) * (u @ wu.T)) @ wd.T).numpy()
+
+
+def moe_weights(cfg, r, same_experts=False):
+    E, Fe, h = cfg.n_experts, cfg.expert_ffn, cfg.hidden
+    w = dict(w_router=r.normal(0, 1.0, (E, h)), w_expert_gate_up=r.normal(0, 0.3, (E, 2 * Fe, h)),
+             w_expert_down=r.normal(0, 0.3, (E, h, Fe)))
+    if same_experts:
+        w["w_expert_gate_up"][:] = w["w_expert_gate_up"][0]
+        w["w_expert_down"][:] = w["w_expert_down"][0]
+    if cfg.shared_ffn:
+        w["w_shared_gate_up"] = r.normal(0, 0.3, (2 * cfg.shared_ffn, h))
+        w["w_shared_down"] = r.normal(0, 0.3, (h, cfg.shared_ffn))
+    return w
+
+
+def test_swiglu_matches_torch():
+    r = np.random.default_rng(3)
+    u, wgu, wd = r.normal(size=(5, 16)), r.normal(size=(24, 16)), r.normal(size=(16, 12))
+    np.testing.assert_allclose(fo.swiglu(u, wgu, wd), torch_swiglu(u, wgu, wd), rtol=1e-12, atol=1e-12)
+
+
+def test_route_hand_cases():
+    cfg = tiny_cfg(n_experts=4, experts_per_token=2, expert_ffn=8, route_scale=1.0)
+    ch, wt = fo.route(cfg, np.log(np.array([0.5, 0.25, 0.125, 0.125])))
+    assert ch == [0, 1] and np.allclose(wt, [2 / 3, 1 / 3])
+    ch, wt = fo.route(cfg, np.array([0.0, 1.0, 1.0, 1.0]))                   # ties: lower expert first
+    assert ch == [1, 2] and np.allclose(wt, [0.5, 0.5])
+    cfg.route_scale = 2.5
+    ch, wt = fo.route(cfg, np.log(np.array([0.5, 0.25, 0.125, 0.125])), forced=[3, 0])
+    assert ch == [3, 0] and np.allclose(wt, [2.5 * 0.2, 2.5 * 0.8])           # forced list, in its own order
+    cfg.experts_per_token = 4
+    ch, wt = fo.route(cfg, np.array([0.3, -2.0, 5.0, 0.1]))
+    assert ch == [2, 0, 3, 1] and abs(sum(wt) - 2.5) < 1e-12                  # k = E: the plain softmax, scaled
+
+
+@pytest.mark.parametrize("E,k,Fs", [(1, 1, 0), (6, 2, 0), (8, 3, 12), (4, 4, 8)])
+def test_moe_ffn_against_masked_dense_formulation_in_torch(E, k, Fs):
+    """Independent statement: gates = top-k of the softmax (torch.topk), renormalised; every expert runs on every row and
+    the outputs are mixed with the gate matrix."""
+    r = np.random.default_rng(10 * E + k)
+    cfg = tiny_cfg(n_experts=E, experts_per_token=k, expert_ffn=12, shared_ffn=Fs, route_scale=1.7)
+    w = moe_weights(cfg, r)
+    u = r.normal(size=(9, cfg.hidden))
+    y, experts, weights = fo.moe_ffn(cfg, w, u)
+    tu = torch.from_numpy(u)
+    probs = torch.softmax(tu @ torch.from_numpy(w["w_router"]).T, dim=-1)
+    val, idx = torch.topk(probs, k, dim=-1)
+    gates = torch.zeros_like(probs).scatter(1, idx, val / val.sum(-1, keepdim=True)) * float(np.float32(1.7))
+    want = sum(gates[:, e:e + 1].numpy() * torch_swiglu(u, w["w_expert_gate_up"][e], w["w_expert_down"][e]) for e in range(E))
+    if Fs:
+        want = want + torch_swiglu(u, w["w_shared_gate_up"], w["w_shared_down"])
+    np.testing.assert_allclose(y, want, rtol=1e-10, atol=1e-10)
+    assert all(sorted(experts[i]) == sorted(idx[i].tolist()) for i in range(9))
+    assert all(abs(sum(wt) - float(np.float32(1.7))) < 1e-12 and all(a >= b for a, b in zip(wt, wt[1:])) for wt in weights)
+    if E == 1:   # one expert: the dense feed-forward with that expert's weights
+        np.testing.assert_allclose(y, float(np.float32(1.7)) * torch_swiglu(u, w["w_expert_gate_up"][0], w["w_expert_down"][0]), rtol=1e-10)
+
+
+def test_moe_forced_routing_uses_the_given_experts():
+    r = np.random.default_rng(77)
+    cfg = tiny_cfg(n_experts=5, experts_per_token=2, expert_ffn=12)
+    w = moe_weights(cfg, r)
+    u = r.normal(size=(4, cfg.hidden))
+    forced = [[4, 0], [1, 2], [3, 4], [0, 1]]
+    y, experts, weights = fo.moe_ffn(cfg, w, u, forced)
+    assert experts == forced
+    p = torch.softmax(torch.from_numpy(u @ w["w_router"].T), dim=-1).numpy()
+    for i in range(4):
+        a, b = forced[i]
+        g = p[i, [a, b]] / p[i, [a, b]].sum()
+        want = g[0] * torch_swiglu(u[i:i + 1], w["w_expert_gate_up"][a], w["w_expert_down"][a]) + \
+            g[1] * torch_swiglu(u[i:i + 1], w["w_expert_gate_up"][b], w["w_expert_down"][b])
+        np.testing.assert_allclose(y[i], want[0], rtol=1e-10, atol=1e-12)
+
+
+@pytest.mark.parametrize("first", [0, 1])
+def test_step_with_identical_experts_equals_the_dense_model(first):
+    """Experts that share one set of weights make the routing irrelevant (the weights sum to one): the whole step,
+    decisions included, must equal the step of the dense model with that feed-forward."""
+    dense = tiny_cfg(ffn=24, keep_ratio=0.5)
+    moe = tiny_cfg(ffn=24, keep_ratio=0.5, n_experts=4, experts_per_token=2, expert_ffn=24, first_moe_layer=first)
+    Wd = tiny_weights(dense, seed=5)
+    layers = []
+    for l in range(dense.n_layers):
+        w = dict(Wd.layer(l))
+        w["w_router"] = np.random.default_rng(l).normal(size=(4, dense.hidden))
+        w["w_expert_gate_up"] = np.stack([w["w_gate_up"]] * 4)
+        w["w_expert_down"] = np.stack([w["w_down"]] * 4)
+        layers.append(w)
+    Wm = fo.Weights(Wd.embed, Wd.lm_head, Wd.final_norm, lambda l: layers[l])
+    pd, sd, _ = tiny_batch(dense, Wd, [5, 11])
+    pm, sm, _ = tiny_batch(moe, Wm, [5, 11])
+    for step in range(3):
+        td, tm = fo.focus_step(dense, Wd, pd, sd), fo.focus_step(moe, Wm, pm, sm)
+        assert td.keep == tm.keep and td.committed == tm.committed
+        np.testing.assert_allclose(tm.logits, td.logits, rtol=1e-9, atol=1e-9)
+        assert sorted(tm.route) == list(range(first, 3)) and all(len(v[0]) == 2 for v in tm.route[2].values())
+        assert first or len(tm.route[0]) == 2 * moe.block_size           # layers below e run on the whole block
+        assert set(tm.route[2]) == set(tm.row_map) == set(tm.route[1])      # the feed-forward of layer e runs after the gather
