@@ -114,6 +114,8 @@ def permutation(seed: int, tensor_id: int, n: int) -> List[int]:
 # tensor ids
 TID_EMBED, TID_LM_HEAD, TID_KV, TID_PROMPT, TID_PREFIX_LEN, TID_K_OVERRIDE, TID_PAGE_PERM = 1, 2, 3, 4, 5, 6, 7
 TID_LAYER0 = 16           # + 8*layer + {0: w_qkv, 1: w_o, 2: w_gate_up, 3: w_down}
+TID_ROUTE_OVERRIDE = 8
+TID_MOE0 = 1 << 20        # + 8*layer + {0: w_router, 1: w_expert_gate_up, 2: w_expert_down, 3: w_shared_gate_up, 4: w_shared_down}
 WEIGHT_STD = 0.02
 KV_STD = 1.0
 
@@ -153,6 +155,12 @@ class Workload:
     intra_block_cache: int = 0  # 1 = delayed intra-block K/V cache with the neighbour-aware stability criterion
     selection: int = 0          # 0 TOP, 1 RANDOM, 2 BOTTOM pick of the K candidates
     selection_seed: int = 0
+    n_experts: int = 0          # mixture-of-experts feed-forward from first_moe_layer on (0 = dense model)
+    experts_per_token: int = 0
+    expert_ffn: int = 0
+    shared_ffn: int = 0
+    first_moe_layer: int = 0
+    route_scale: float = 1.0
     steps: int = 1
     shuffle_pages: bool = False
     extra_blocks: int = 0       # further blocks each sequence will generate (pages and positions are planned for them)
@@ -213,6 +221,36 @@ class Workload:
         shape = self.weight_shapes()[which]
         out = torch.empty(shape, dtype=self.torch_dtype, device=device)
         return fill_normal_(out, self.seed, TID_LAYER0 + 8 * layer + order[which], WEIGHT_STD)
+
+    def is_moe_layer(self, layer: int) -> bool:
+        return self.n_experts > 0 and layer >= self.first_moe_layer
+
+    def moe_weight_shapes(self) -> Dict[str, tuple]:
+        E, Fe, Fs, h = self.n_experts, self.expert_ffn, self.shared_ffn, self.hidden
+        shapes = {"w_router": (E, h), "w_expert_gate_up": (E, 2 * Fe, h), "w_expert_down": (E, h, Fe)}
+        if Fs:
+            shapes.update({"w_shared_gate_up": (2 * Fs, h), "w_shared_down": (h, Fs)})
+        return shapes
+
+    def moe_weight(self, layer: int, which: str, device="cpu") -> torch.Tensor:
+        """Router rows are drawn with a larger spread (std 0.1) so that the routing probabilities are well apart."""
+        order = {"w_router": 0, "w_expert_gate_up": 1, "w_expert_down": 2, "w_shared_gate_up": 3, "w_shared_down": 4}
+        out = torch.empty(self.moe_weight_shapes()[which], dtype=self.torch_dtype, device=device)
+        return fill_normal_(out, self.seed, TID_MOE0 + 8 * layer + order[which], 0.1 if which == "w_router" else WEIGHT_STD)
+
+    def route_override(self, n_seq: Optional[int] = None) -> List[List[List[int]]]:
+        """Seeded forced routing [layer][row id b * B + p] -> experts_per_token distinct experts (teacher forcing)."""
+        n = (self.batch if n_seq is None else n_seq) * self.block_size
+        key = stream_key(self.seed, TID_ROUTE_OVERRIDE)
+        out = []
+        for l in range(self.n_layers):
+            rows = []
+            for r in range(n):
+                base = (l * n + r) * self.n_experts
+                ranked = sorted(range(self.n_experts), key=lambda e: (hash_py(key, base + e), e))
+                rows.append(ranked[:self.experts_per_token])
+            out.append(rows)
+        return out
 
     def embed(self, device="cpu") -> torch.Tensor:
         out = torch.empty((self.vocab, self.hidden), dtype=self.torch_dtype, device=device)

@@ -84,6 +84,18 @@ typedef struct focus_config {
                                to the pick unchanged */
   uint32_t selection_seed;  /* RANDOM: position j of slot s is ranked by output number c + 1 of the SplitMix64 generator
                                started at selection_seed, c = (s * 2^32 + total_steps of the slot before the step) * 64 + j */
+  /* Mixture-of-experts feed-forward (the second model of Sec. 5.1 is an MoE; the paper does not spell out its layer, this is
+     the common token-choice one).  In layers first_moe_layer .. n_layers - 1 a row's feed-forward is
+       route_scale * sum_j g_j * Expert_{e_j}(u)  +  Shared(u)
+     where u is the normalised row, e_1 .. e_k are the k experts with the largest router logit w_router u (descending; ties:
+     lower expert), g = softmax over all E logits restricted to the chosen ones and renormalised to sum to one, and every
+     expert (the shared one too) is a SwiGLU feed-forward.  Layers below first_moe_layer keep the dense feed-forward. */
+  int32_t n_experts;        /* E, 0..512; 0 = dense model, the members below are ignored */
+  int32_t experts_per_token;/* k, 1..min(E, 32) */
+  int32_t expert_ffn;       /* F_e, inner width of a routed expert */
+  int32_t shared_ffn;       /* F_s, inner width of the shared expert; 0 = none */
+  int32_t first_moe_layer;  /* 0..n_layers */
+  float   route_scale;
 } focus_config;
 
 /* Device pointers.  The per-layer members are HOST arrays of n_layers device pointers. */
@@ -97,6 +109,13 @@ typedef struct focus_weights {
   const void *const *mlp_norm;    /* [hidden] */
   const void *const *w_gate_up;   /* [2 F, hidden] */
   const void *const *w_down;      /* [hidden, F] */
+  /* mixture-of-experts layers (n_experts > 0; entries of dense layers are ignored, and so are w_gate_up / w_down entries of
+     mixture-of-experts layers) */
+  const void *const *w_router;          /* [E, hidden] */
+  const void *const *w_expert_gate_up;  /* [E, 2 F_e, hidden]: per expert F_e gate rows, then F_e up rows */
+  const void *const *w_expert_down;     /* [E, hidden, F_e] */
+  const void *const *w_shared_gate_up;  /* [2 F_s, hidden] (shared_ffn > 0) */
+  const void *const *w_shared_down;     /* [hidden, F_s] */
 } focus_weights;
 
 /* Optional outputs of a step; every member is a caller-allocated device pointer or NULL.  n = n_seq,
@@ -118,6 +137,9 @@ typedef struct focus_step_out {
                                intra-block cache, the rows of the positions that are not frozen, packed in batch order */
   float    *hidden_packed;  /* [n * B, hidden]  first T' rows valid: residual stream after the last layer */
   float    *logits;         /* [n * B, vocab]   first T' rows valid */
+  int32_t  *route_experts;  /* [n_layers, max_batch * B, k]  mixture-of-experts layers: the experts row b * B + p used, in the
+                               order of their weights; written for the rows that ran in the layer, other entries untouched */
+  float    *route_weights;  /* [n_layers, max_batch * B, k]  their mixing weights (route_scale included) */
 } focus_step_out;
 
 /* Host copy of one slot's block state (App. E.3.1 plus the block's tokens). */
@@ -191,6 +213,13 @@ int focus_run_layers(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int3
  * Enqueues only (no host synchronisation). */
 int focus_finalize_blocks(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32_t *seq_slot, int32_t *finalized);
 
+/* Teacher forcing for mixture-of-experts layers: from now on focus_step and focus_run_layers use, for the row of block
+ * position p of batch entry b in layer l, the experts experts[(l * max_batch * B + b * B + p) * k + j], j < k (distinct,
+ * in 0..E-1; out-of-range values are clamped), with weights computed from the router logits as for the router's own pick.
+ * Prefill and block finalisation always route by themselves.  NULL switches it off.
+ *   experts       device [n_layers, max_batch * B, k], borrowed until replaced */
+int focus_set_route_override(focus_ctx *ctx, const int32_t *experts);
+
 /* Stage entry: confidence-based commit (Alg. 1 Decode_and_Verify, App. E.3.1 statistics) on caller-given
  * confidences.  Updates the slot state and writes out->tokens, mask_bits, n_decoded.
  *   keep_bits     device [n_seq]; cu_seqlens device [n_seq + 1]; conf, argmax device [cu_seqlens[n_seq]] */
@@ -211,7 +240,8 @@ enum { FOCUS_KC_GEMM = 0,      /* dense projections: QKV, O, gate/up, down, lm_h
        FOCUS_KC_EVICT = 2,     /* importance, budget + selection, scan, gather */
        FOCUS_KC_POINTWISE = 3, /* embedding, RMSNorm, rotary + K/V write, SiLU*up */
        FOCUS_KC_DECODE = 4,    /* confidence over the vocabulary, commit */
-       FOCUS_KC_COUNT = 5 };
+       FOCUS_KC_ROUTE = 5,     /* mixture-of-experts: picks, sorting by expert, weighted sum (the expert projections are GEMM) */
+       FOCUS_KC_COUNT = 6 };
 int focus_set_timing(focus_ctx *ctx, int32_t enable);
 int focus_get_kernel_time(focus_ctx *ctx, int32_t kernel_class, float *total_ms, int32_t *launches);
 

@@ -432,7 +432,7 @@ def moe_ffn(cfg: OracleConfig, w: Dict[str, np.ndarray], u: np.ndarray, forced=N
     token-choice layer.  A linear router scores E experts per row, route() picks k of them with weights, each
     expert is a SwiGLU feed-forward of inner width F_e, the row's output is the weighted sum of its experts'
     outputs plus, when F_s > 0, a shared SwiGLU expert that every row goes through.
-    forced[i]: expert list to use for row i instead of the router's pick.  Returns (y, experts, weights)."""
+    forced[i]: expert list to use for row i instead of the router's pick.  Returns (y, experts, weights, router logits)."""
     r = u.shape[0]
     logits = u @ w["w_router"].T
     y = np.zeros((r, cfg.hidden))
@@ -445,7 +445,7 @@ def moe_ffn(cfg: OracleConfig, w: Dict[str, np.ndarray], u: np.ndarray, forced=N
             y[i] += g * swiglu(u[i:i + 1], w["w_expert_gate_up"][e], w["w_expert_down"][e])[0]
     if cfg.shared_ffn > 0:
         y += swiglu(u, w["w_shared_gate_up"], w["w_shared_down"])
-    return y, experts, weights
+    return y, experts, weights, logits
 
 
 def _finish_layer(cfg: OracleConfig, w: Dict[str, np.ndarray], X: np.ndarray, attn: np.ndarray,
@@ -456,10 +456,10 @@ def _finish_layer(cfg: OracleConfig, w: Dict[str, np.ndarray], X: np.ndarray, at
     u = rmsnorm(X, w["mlp_norm"], cfg.rms_eps)
     if cfg.n_experts > 0 and layer >= cfg.first_moe_layer:
         forced = None if route_override is None else [route_override[layer][rid] for rid in row_ids]
-        y, experts, weights = moe_ffn(cfg, w, u, forced)
+        y, experts, weights, logits = moe_ffn(cfg, w, u, forced)
         if route_log is not None:
             for i, rid in enumerate(row_ids):
-                route_log.setdefault(layer, {})[rid] = (experts[i], weights[i])
+                route_log.setdefault(layer, {})[rid] = (experts[i], weights[i], logits[i])
         return X + y
     return X + swiglu(u, w["w_gate_up"], w["w_down"])
 
@@ -483,7 +483,7 @@ class StepTrace:
     argmax: Optional[np.ndarray] = None
     committed: List[List[int]] = field(default_factory=list)  # per sequence, positions unmasked this step
     n_decoded: List[int] = field(default_factory=list)
-    route: Dict[int, Dict[int, tuple]] = field(default_factory=dict)   # MoE layer -> row id b * B + p -> (experts, weights)
+    route: Dict[int, Dict[int, tuple]] = field(default_factory=dict)   # MoE layer -> row id b * B + p -> (experts, weights, router logits)
 
 
 def focus_step(cfg: OracleConfig, W: Weights, pool: KVPool, seqs: List[SeqState],

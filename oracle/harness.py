@@ -21,7 +21,9 @@ def oracle_config(wl: Workload, **over) -> fo.OracleConfig:
         evict_layer=wl.evict_layer, importance_mode=wl.importance_mode, maxpool_k=wl.maxpool_k,
         budget_mode=wl.budget_mode, topk=wl.topk, keep_ratio=wl.keep_ratio, alpha=wl.alpha,
         constraints=wl.constraints, conf_threshold=wl.conf_threshold, intra_block_cache=wl.intra_block_cache,
-        selection=wl.selection, selection_seed=wl.selection_seed)
+        selection=wl.selection, selection_seed=wl.selection_seed, n_experts=wl.n_experts,
+        experts_per_token=wl.experts_per_token, expert_ffn=wl.expert_ffn, shared_ffn=wl.shared_ffn,
+        first_moe_layer=wl.first_moe_layer, route_scale=wl.route_scale)
     for k, v in over.items():
         setattr(cfg, k, v)
     return cfg
@@ -55,7 +57,10 @@ def oracle_weights(wl: Workload, cache_layers: bool = True, lazy_embed: bool = F
     def layer(l: int):
         if l in cache:
             return cache[l]
-        w = {k: _f64(wl.layer_weight(l, k)) for k in ("w_qkv", "w_o", "w_gate_up", "w_down")}
+        moe = wl.is_moe_layer(l)
+        w = {k: _f64(wl.layer_weight(l, k)) for k in (("w_qkv", "w_o") if moe else ("w_qkv", "w_o", "w_gate_up", "w_down"))}
+        if moe:
+            w.update({k: _f64(wl.moe_weight(l, k)) for k in wl.moe_weight_shapes()})
         w["attn_norm"] = ones
         w["mlp_norm"] = ones
         if cache_layers:

@@ -18,8 +18,8 @@ LIB_PATH = os.path.join(_HERE, "libfocus.so")
 FOCUS_OK, FOCUS_EINVAL, FOCUS_ENOMEM, FOCUS_EHIP = 0, -1, -2, -3
 FOCUS_F32, FOCUS_BF16 = 0, 1
 FOCUS_MAX_BLOCK = 64
-KC_GEMM, KC_ATTENTION, KC_EVICT, KC_POINTWISE, KC_DECODE, KC_COUNT = 0, 1, 2, 3, 4, 5
-KC_NAMES = ["gemm", "attention", "evict", "pointwise", "decode"]
+KC_GEMM, KC_ATTENTION, KC_EVICT, KC_POINTWISE, KC_DECODE, KC_ROUTE, KC_COUNT = 0, 1, 2, 3, 4, 5, 6
+KC_NAMES = ["gemm", "attention", "evict", "pointwise", "decode", "route"]
 
 
 class focus_config(C.Structure):
@@ -31,16 +31,21 @@ class focus_config(C.Structure):
                                          "topk")] + \
                [("keep_ratio", C.c_float), ("alpha", C.c_float), ("constraints", C.c_int32),
                 ("conf_threshold", C.c_float), ("intra_block_cache", C.c_int32), ("selection", C.c_int32),
-                ("selection_seed", C.c_uint32)]
+                ("selection_seed", C.c_uint32)] + \
+               [(n, C.c_int32) for n in ("n_experts", "experts_per_token", "expert_ffn", "shared_ffn", "first_moe_layer")] + \
+               [("route_scale", C.c_float)]
 
 
 class focus_weights(C.Structure):
     _fields_ = [("embed", C.c_void_p), ("lm_head", C.c_void_p), ("final_norm", C.c_void_p)] + \
-               [(n, C.POINTER(C.c_void_p)) for n in ("attn_norm", "w_qkv", "w_o", "mlp_norm", "w_gate_up", "w_down")]
+               [(n, C.POINTER(C.c_void_p)) for n in ("attn_norm", "w_qkv", "w_o", "mlp_norm", "w_gate_up", "w_down",
+                                                     "w_router", "w_expert_gate_up", "w_expert_down", "w_shared_gate_up",
+                                                     "w_shared_down")]
 
 
 _OUT_FIELDS = ("tokens", "mask_bits", "n_decoded", "importance_prev", "importance", "delta_I", "K", "keep_bits",
-               "cu_seqlens", "row_map", "conf", "argmax", "hidden_full", "hidden_packed", "logits")
+               "cu_seqlens", "row_map", "conf", "argmax", "hidden_full", "hidden_packed", "logits", "route_experts",
+               "route_weights")
 
 
 class focus_step_out(C.Structure):
@@ -74,6 +79,7 @@ def load_library() -> C.CDLL:
         "focus_commit": [P, P, I, P, P, P, P, P, C.POINTER(focus_step_out)],
         "focus_run_layers": [P, P, I, P, P, P, I, I, P],
         "focus_finalize_blocks": [P, P, I, P, P],
+        "focus_set_route_override": [P, P],
         "focus_get_state": [P, I, C.POINTER(focus_seq_state)],
         "focus_set_state": [P, I, C.POINTER(focus_seq_state)],
         "focus_set_timing": [P, I],
@@ -89,7 +95,7 @@ def load_library() -> C.CDLL:
 
 _lib = load_library()
 EXPORTS = ["focus_workspace_bytes", "focus_kv_pool_bytes", "focus_init", "focus_prefill_kv", "focus_step",
-           "focus_select_compact", "focus_commit", "focus_run_layers", "focus_finalize_blocks", "focus_get_state", "focus_set_state", "focus_set_timing",
+           "focus_select_compact", "focus_commit", "focus_run_layers", "focus_finalize_blocks", "focus_set_route_override", "focus_get_state", "focus_set_state", "focus_set_timing",
            "focus_get_kernel_time", "focus_free", "focus_last_error"]
 
 
@@ -141,8 +147,11 @@ class Focus:
         w = focus_weights()
         w.embed, w.lm_head, w.final_norm = embed.data_ptr(), lm_head.data_ptr(), final_norm.data_ptr()
         self._arrays = {}
-        for name in ("attn_norm", "w_qkv", "w_o", "mlp_norm", "w_gate_up", "w_down"):
-            arr = (C.c_void_p * cfg.n_layers)(*[l[name].data_ptr() for l in layers])
+        names = ["attn_norm", "w_qkv", "w_o", "mlp_norm", "w_gate_up", "w_down"]
+        if cfg.n_experts > 0:
+            names += ["w_router", "w_expert_gate_up", "w_expert_down"] + (["w_shared_gate_up", "w_shared_down"] if cfg.shared_ffn else [])
+        for name in names:
+            arr = (C.c_void_p * cfg.n_layers)(*[l[name].data_ptr() if name in l else None for l in layers])
             self._arrays[name] = arr
             setattr(w, name, arr)
         self._ctx = C.c_void_p()
@@ -186,6 +195,10 @@ class Focus:
     def focus_finalize_blocks(self, n_seq: int, finalized: Optional[torch.Tensor] = None, seq_slot: Optional[torch.Tensor] = None,
                               stream=None):
         _check(_lib.focus_finalize_blocks(self._ctx, self._stream(stream), n_seq, _ptr(seq_slot), _ptr(finalized)), self._ctx)
+
+    def focus_set_route_override(self, experts: Optional[torch.Tensor]):
+        self._route_override = experts       # borrowed by the library
+        _check(_lib.focus_set_route_override(self._ctx, _ptr(experts)), self._ctx)
 
     def focus_get_state(self, slot: int) -> focus_seq_state:
         st = focus_seq_state()

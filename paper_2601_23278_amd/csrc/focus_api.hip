@@ -23,8 +23,11 @@ struct Plan {
   size_t off_partial, off_delta, off_K, off_keep, off_n_keep, off_vis, off_cu, off_cu_full, off_row_map,
       off_row_map_full, off_total, off_total_full, off_conf, off_argmax, off_prompt, off_prompt_off, off_prompt_len,
       off_slot_list, off_part_o, off_part_ml, off_order, off_uncached, off_finalized;
+  // mixture-of-experts work buffers (zero-sized for a dense model)
+  size_t off_moe_logits, off_moe_idx, off_moe_w, off_moe_list, off_moe_count, off_moe_offs, off_moe_tile_e, off_moe_tile_m0,
+      off_moe_ntiles, off_moe_pos, off_moe_arow, off_moe_aexp, off_moe_act, off_moe_y;
   size_t bytes, part_entries;
-  int table_stride, max_rows, max_pos;
+  int table_stride, max_rows, max_pos, moe_tile_slots;
 };
 
 size_t esize(int dtype) { return dtype == FOCUS_F32 ? 4 : 2; }
@@ -54,8 +57,9 @@ Plan make_plan(const focus_config &c) {
   p.off_qkv = take(rows * qkv_w * es);
   p.off_q_p = take(rows * q_w * es);
   p.off_attn = take(rows * q_w * es);
-  p.off_gate_up = take(rows * 2 * c.ffn * es);
-  p.off_act = take(rows * c.ffn * es);
+  const size_t ffn_w = c.n_experts > 0 ? (size_t)std::max(c.ffn, c.shared_ffn) : (size_t)c.ffn;   // dense and shared-expert feed-forward
+  p.off_gate_up = take(rows * 2 * ffn_w * es);
+  p.off_act = take(rows * ffn_w * es);
   p.off_logits = take(rows * (size_t)c.vocab * 4);
   p.off_partial = take(2 * nb * c.n_q_heads * B * 4);
   p.off_delta = take(rows * 4);
@@ -83,6 +87,24 @@ Plan make_plan(const focus_config &c) {
   p.off_order = take(nb * 4);
   p.off_uncached = take(nb * 8);
   p.off_finalized = take(nb * 4);
+  if (c.n_experts > 0) {
+    const size_t E = c.n_experts, ent = rows * c.experts_per_token;
+    p.moe_tile_slots = (int)(ent / fk::kMoeTileRows + E);
+    p.off_moe_logits = take(rows * E * 4);
+    p.off_moe_idx = take((ent + 1024) * 4);          // read in 1024-entry trips
+    p.off_moe_w = take(ent * 4);
+    p.off_moe_list = take(E * rows * 4);
+    p.off_moe_count = take(E * 4);
+    p.off_moe_offs = take((E + 1) * 4);
+    p.off_moe_tile_e = take((size_t)p.moe_tile_slots * 4);
+    p.off_moe_tile_m0 = take((size_t)p.moe_tile_slots * 4);
+    p.off_moe_ntiles = take(4);
+    p.off_moe_pos = take(ent * 4);
+    p.off_moe_arow = take(ent * 4);
+    p.off_moe_aexp = take(ent * 4);
+    p.off_moe_act = take(ent * c.expert_ffn * es);
+    p.off_moe_y = take(ent * c.hidden * 4);
+  }
   p.bytes = at;
   return p;
 }
@@ -106,6 +128,14 @@ const char *check_config(const focus_config &c) {
   if (c.intra_block_cache != 0 && c.intra_block_cache != 1) return "intra_block_cache must be 0 or 1";
   if (c.selection < FOCUS_SELECT_TOP || c.selection > FOCUS_SELECT_BOTTOM) return "selection must be a FOCUS_SELECT_* value";
   if (!(c.rms_eps > 0.f) || !(c.rope_base > 1.f)) return "rms_eps must be > 0 and rope_base > 1";
+  if (c.n_experts < 0 || c.n_experts > 512) return "n_experts must be in 0..512";
+  if (c.n_experts > 0) {
+    if (c.experts_per_token < 1 || c.experts_per_token > c.n_experts || c.experts_per_token > 32) return "experts_per_token must be in 1..min(n_experts, 32)";
+    if (c.expert_ffn < 8 || c.expert_ffn % 8 || c.shared_ffn < 0 || c.shared_ffn % 8) return "expert_ffn and shared_ffn must be multiples of 8";
+    if (c.first_moe_layer < 0 || c.first_moe_layer > c.n_layers) return "first_moe_layer must be in 0..n_layers";
+    if (!(c.route_scale > 0.f)) return "route_scale must be > 0";
+    if ((double)c.max_batch * c.block_size * c.experts_per_token > (double)(1u << 26)) return "max_batch * block_size * experts_per_token too large";
+  }
   return nullptr;
 }
 
@@ -118,6 +148,12 @@ struct focus_ctx {
   char *kv_pool;
   const void *embed, *lm_head, *final_norm;
   std::vector<const void *> attn_norm, w_qkv, w_o, mlp_norm, w_gate_up, w_down;
+  std::vector<const void *> w_router, w_expert_gate_up, w_expert_down, w_shared_gate_up, w_shared_down;
+  // forced routing (focus_set_route_override) and the routing outputs of the running step; planes of max_batch * B * k per layer
+  const int32_t *route_override = nullptr;
+  int32_t *out_route_experts = nullptr;
+  float *out_route_weights = nullptr;
+  bool route_by_row_id = false;         // inside focus_step / focus_run_layers: rows are block positions of the step's batch
   std::string error;
   // timing
   bool timing = false;
@@ -134,6 +170,7 @@ struct focus_ctx {
             at<int64_t>(plan.off_token_sum), at<int32_t>(plan.off_total_steps), cfg.max_batch,
             at<int32_t>(plan.off_page_count), cfg.max_prefix_len, at<uint64_t>(plan.off_cached)};
   }
+  bool moe_layer(int l) const { return cfg.n_experts > 0 && l >= cfg.first_moe_layer; }
   fk::KvLayer kv_layer(int l) const {
     size_t layer_bytes = (size_t)cfg.n_pages * 2 * cfg.n_kv_heads * cfg.page_size * cfg.head_dim * esize(cfg.dtype);
     return {kv_pool + (size_t)l * layer_bytes, cfg.page_size, cfg.n_kv_heads, cfg.head_dim};
@@ -175,6 +212,16 @@ struct Timed {
   }
 };
 
+// While alive, the rows of the layers are block positions of the caller's batch: forced routing applies and the routing
+// outputs are written.  Prefill and block finalisation run without it.
+struct RouteScope {
+  focus_ctx *c;
+  RouteScope(focus_ctx *c_, int32_t *experts, float *weights) : c(c_) {
+    c->route_by_row_id = true; c->out_route_experts = experts; c->out_route_weights = weights;
+  }
+  ~RouteScope() { c->route_by_row_id = false; c->out_route_experts = nullptr; c->out_route_weights = nullptr; }
+};
+
 struct RowSet {        // a set of rows the layers run on
   fk::Rows rows;
   fk::RowIndex ri;
@@ -200,13 +247,16 @@ void layer_qkv(focus_ctx *c, hipStream_t s, int l, const RowSet &rs, const float
     fk::rope_kv_write(s, g.dtype, qkv, g.n_q_heads, rs.rows, rs.ri, c->slots(), c->kv_layer(l), c->at<float2>(c->plan.off_rope), rs.n_seq, rs.cu); }
 }
 
-// attention -> O projection (+residual) -> rmsnorm -> gate/up -> SiLU*up -> down (+residual).
+void swiglu_ffn(focus_ctx *c, hipStream_t s, const RowSet &rs, const void *normed, const void *w_gate_up, const void *w_down, int ffn,
+                float *resid, fk::Warm warm_after);
+void moe_ffn(focus_ctx *c, hipStream_t s, int l, const RowSet &rs, float *resid, const void *normed);
+
+// attention -> O projection (+residual) -> rmsnorm -> feed-forward (+residual).
 void layer_rest(focus_ctx *c, hipStream_t s, int l, const RowSet &rs, float *resid, const void *q, int q_stride,
                 const uint64_t *vis_by_b) {
   const focus_config &g = c->cfg;
   const int q_w = g.n_q_heads * g.head_dim;
   void *normed = c->at<char>(c->plan.off_normed), *attn = c->at<char>(c->plan.off_attn);
-  void *gate_up = c->at<char>(c->plan.off_gate_up), *act = c->at<char>(c->plan.off_act);
   { Timed t(c, s, FOCUS_KC_ATTENTION);
     fk::AttnArgs a{};
     a.dtype = g.dtype; a.q = q; a.q_stride = q_stride; a.n_q_heads = g.n_q_heads; a.n_seq = rs.n_seq; a.cu = rs.cu;
@@ -221,18 +271,58 @@ void layer_rest(focus_ctx *c, hipStream_t s, int l, const RowSet &rs, float *res
     fk::attention(s, a); }
   { Timed t(c, s, FOCUS_KC_GEMM); fk::gemm(s, g.dtype, attn, c->w_o[l], g.hidden, q_w, rs.rows, fk::EPI_ADD_F32, resid, g.hidden); }
   { Timed t(c, s, FOCUS_KC_POINTWISE); fk::rmsnorm(s, g.dtype, resid, c->mlp_norm[l], normed, g.hidden, g.rms_eps, rs.rows); }
-  if (fk::gemm_fuses_silu_mul(g.dtype, normed, c->w_gate_up[l], 2 * g.ffn, g.hidden)) {
-    Timed t(c, s, FOCUS_KC_GEMM);
-    fk::gemm(s, g.dtype, normed, c->w_gate_up[l], 2 * g.ffn, g.hidden, rs.rows, fk::EPI_SILU_MUL, act, g.ffn,
-             fk::Warm{c->w_down[l], (size_t)g.hidden * g.ffn * esize(g.dtype)});
-  } else {
-    { Timed t(c, s, FOCUS_KC_GEMM); fk::gemm(s, g.dtype, normed, c->w_gate_up[l], 2 * g.ffn, g.hidden, rs.rows, fk::EPI_STORE, gate_up, 2 * g.ffn); }
-    { Timed t(c, s, FOCUS_KC_POINTWISE); fk::silu_mul(s, g.dtype, gate_up, act, g.ffn, rs.rows); }
+  const size_t qkv_bytes = (size_t)(g.n_q_heads + 2 * g.n_kv_heads) * g.head_dim * g.hidden * esize(g.dtype);
+  const fk::Warm next_qkv = l + 1 < g.n_layers ? fk::Warm{c->w_qkv[l + 1], qkv_bytes} : fk::Warm();
+  if (c->moe_layer(l)) {
+    moe_ffn(c, s, l, rs, resid, normed);
+    return;
   }
+  swiglu_ffn(c, s, rs, normed, c->w_gate_up[l], c->w_down[l], g.ffn, resid, next_qkv);
+}
+
+// SwiGLU feed-forward on normalised rows, added to the residual stream: gate/up -> SiLU*up -> down.
+void swiglu_ffn(focus_ctx *c, hipStream_t s, const RowSet &rs, const void *normed, const void *w_gate_up, const void *w_down, int ffn,
+                float *resid, fk::Warm warm_after) {
+  const focus_config &g = c->cfg;
+  void *gate_up = c->at<char>(c->plan.off_gate_up), *act = c->at<char>(c->plan.off_act);
+  if (fk::gemm_fuses_silu_mul(g.dtype, normed, w_gate_up, 2 * ffn, g.hidden)) {
+    Timed t(c, s, FOCUS_KC_GEMM);
+    fk::gemm(s, g.dtype, normed, w_gate_up, 2 * ffn, g.hidden, rs.rows, fk::EPI_SILU_MUL, act, ffn,
+             fk::Warm{w_down, (size_t)g.hidden * ffn * esize(g.dtype)});
+  } else {
+    { Timed t(c, s, FOCUS_KC_GEMM); fk::gemm(s, g.dtype, normed, w_gate_up, 2 * ffn, g.hidden, rs.rows, fk::EPI_STORE, gate_up, 2 * ffn); }
+    { Timed t(c, s, FOCUS_KC_POINTWISE); fk::silu_mul(s, g.dtype, gate_up, act, ffn, rs.rows); }
+  }
+  { Timed t(c, s, FOCUS_KC_GEMM); fk::gemm(s, g.dtype, act, w_down, g.hidden, ffn, rs.rows, fk::EPI_ADD_F32, resid, g.hidden, warm_after); }
+}
+
+// Mixture-of-experts feed-forward on normalised rows, added to the residual stream: router logits -> picks and weights ->
+// entries sorted by expert -> grouped gate/up and down projections -> weighted sum; plus the shared expert, if any.
+void moe_ffn(focus_ctx *c, hipStream_t s, int l, const RowSet &rs, float *resid, const void *normed) {
+  const focus_config &g = c->cfg;
+  const Plan &pl = c->plan;
+  const size_t plane = (size_t)g.max_batch * g.block_size * g.experts_per_token;
+  fk::MoeArgs a{};
+  a.dtype = g.dtype; a.n_experts = g.n_experts; a.k = g.experts_per_token; a.expert_ffn = g.expert_ffn; a.hidden = g.hidden;
+  a.route_scale = g.route_scale; a.rows = rs.rows; a.row_map = rs.ri.row_map; a.u = normed;
+  a.logits = c->at<float>(pl.off_moe_logits);
+  a.route_override = c->route_by_row_id && c->route_override ? c->route_override + (size_t)l * plane : nullptr;
+  a.topk_idx = c->at<int32_t>(pl.off_moe_idx); a.topk_w = c->at<float>(pl.off_moe_w);
+  a.list = c->at<int32_t>(pl.off_moe_list); a.count = c->at<int32_t>(pl.off_moe_count); a.offs = c->at<int32_t>(pl.off_moe_offs);
+  a.tile_e = c->at<int32_t>(pl.off_moe_tile_e); a.tile_m0 = c->at<int32_t>(pl.off_moe_tile_m0); a.n_tiles = c->at<int32_t>(pl.off_moe_ntiles);
+  a.n_tile_slots = std::min(pl.moe_tile_slots, rs.rows.cap * g.experts_per_token / fk::kMoeTileRows + g.n_experts);
+  a.pos = c->at<int32_t>(pl.off_moe_pos); a.arow = c->at<int32_t>(pl.off_moe_arow); a.aexp = c->at<int32_t>(pl.off_moe_aexp);
+  a.w_gate_up = c->w_expert_gate_up[l]; a.w_down = c->w_expert_down[l];
+  a.act = c->at<char>(pl.off_moe_act); a.y = c->at<float>(pl.off_moe_y); a.resid = resid;
+  a.out_experts = c->route_by_row_id && c->out_route_experts ? c->out_route_experts + (size_t)l * plane : nullptr;
+  a.out_weights = c->route_by_row_id && c->out_route_weights ? c->out_route_weights + (size_t)l * plane : nullptr;
   { Timed t(c, s, FOCUS_KC_GEMM);
-    const size_t qkv_bytes = (size_t)(g.n_q_heads + 2 * g.n_kv_heads) * g.head_dim * g.hidden * esize(g.dtype);
-    fk::gemm(s, g.dtype, act, c->w_down[l], g.hidden, g.ffn, rs.rows, fk::EPI_ADD_F32, resid, g.hidden,
-             l + 1 < g.n_layers ? fk::Warm{c->w_qkv[l + 1], qkv_bytes} : fk::Warm()); }
+    fk::gemm(s, g.dtype, normed, c->w_router[l], g.n_experts, g.hidden, rs.rows, fk::EPI_STORE_F32, c->at<float>(pl.off_moe_logits), g.n_experts); }
+  { Timed t(c, s, FOCUS_KC_ROUTE); fk::moe_route(s, a); fk::moe_group(s, a); }
+  { Timed t(c, s, FOCUS_KC_GEMM); fk::moe_experts(s, a); }
+  // the shared expert adds into the residual stream before the routed sum (both orders are the same sum)
+  if (g.shared_ffn > 0) swiglu_ffn(c, s, rs, normed, c->w_shared_gate_up[l], c->w_shared_down[l], g.shared_ffn, resid, fk::Warm());
+  { Timed t(c, s, FOCUS_KC_ROUTE); fk::moe_combine(s, a); }
 }
 
 void attention_split(const focus_ctx *c, int n_seq, int rows_cap, int *chunk, int *splits) {
@@ -290,12 +380,21 @@ int focus_init(const focus_config *cfg, const focus_weights *w, void *kv_pool, s
                size_t workspace_bytes, focus_ctx **out) {
   if (!cfg || !w || !kv_pool || !workspace || !out) return fail(nullptr, FOCUS_EINVAL, "null argument");
   if (const char *m = check_config(*cfg)) return fail(nullptr, FOCUS_EINVAL, "%s", m);
+  const bool all_moe = cfg->n_experts > 0 && cfg->first_moe_layer == 0;
   if (!w->embed || !w->lm_head || !w->final_norm || !w->attn_norm || !w->w_qkv || !w->w_o || !w->mlp_norm ||
-      !w->w_gate_up || !w->w_down)
+      (!all_moe && (!w->w_gate_up || !w->w_down)))
     return fail(nullptr, FOCUS_EINVAL, "null weight pointer");
-  for (int l = 0; l < cfg->n_layers; ++l)
-    if (!w->attn_norm[l] || !w->w_qkv[l] || !w->w_o[l] || !w->mlp_norm[l] || !w->w_gate_up[l] || !w->w_down[l])
+  const bool moe = cfg->n_experts > 0;
+  if (moe && (!w->w_router || !w->w_expert_gate_up || !w->w_expert_down || (cfg->shared_ffn > 0 && (!w->w_shared_gate_up || !w->w_shared_down))))
+    return fail(nullptr, FOCUS_EINVAL, "null expert weight pointer");
+  for (int l = 0; l < cfg->n_layers; ++l) {
+    const bool ml = moe && l >= cfg->first_moe_layer;
+    if (!w->attn_norm[l] || !w->w_qkv[l] || !w->w_o[l] || !w->mlp_norm[l] || (!ml && (!w->w_gate_up[l] || !w->w_down[l])))
       return fail(nullptr, FOCUS_EINVAL, "null weight pointer in layer %d", l);
+    if (ml && (!w->w_router[l] || !w->w_expert_gate_up[l] || !w->w_expert_down[l] ||
+               (cfg->shared_ffn > 0 && (!w->w_shared_gate_up[l] || !w->w_shared_down[l]))))
+      return fail(nullptr, FOCUS_EINVAL, "null expert weight pointer in layer %d", l);
+  }
   if (((uintptr_t)workspace & 255) || ((uintptr_t)kv_pool & 15)) return fail(nullptr, FOCUS_EINVAL, "workspace must be 256-byte and kv_pool 16-byte aligned");
   Plan plan = make_plan(*cfg);
   size_t need_kv;
@@ -314,8 +413,18 @@ int focus_init(const focus_config *cfg, const focus_weights *w, void *kv_pool, s
   c->w_qkv.assign(w->w_qkv, w->w_qkv + cfg->n_layers);
   c->w_o.assign(w->w_o, w->w_o + cfg->n_layers);
   c->mlp_norm.assign(w->mlp_norm, w->mlp_norm + cfg->n_layers);
-  c->w_gate_up.assign(w->w_gate_up, w->w_gate_up + cfg->n_layers);
-  c->w_down.assign(w->w_down, w->w_down + cfg->n_layers);
+  c->w_gate_up.assign(cfg->n_layers, nullptr);
+  c->w_down.assign(cfg->n_layers, nullptr);
+  for (int l = 0; l < cfg->n_layers && !all_moe; ++l) { c->w_gate_up[l] = w->w_gate_up[l]; c->w_down[l] = w->w_down[l]; }
+  if (moe) {
+    c->w_router.assign(w->w_router, w->w_router + cfg->n_layers);
+    c->w_expert_gate_up.assign(w->w_expert_gate_up, w->w_expert_gate_up + cfg->n_layers);
+    c->w_expert_down.assign(w->w_expert_down, w->w_expert_down + cfg->n_layers);
+    if (cfg->shared_ffn > 0) {
+      c->w_shared_gate_up.assign(w->w_shared_gate_up, w->w_shared_gate_up + cfg->n_layers);
+      c->w_shared_down.assign(w->w_shared_down, w->w_shared_down + cfg->n_layers);
+    }
+  }
 
   // rotary table in fp64 on the host: (cos, sin)(pos * base^(-2i/D)), rounded once to fp32
   const int half = cfg->head_dim / 2;
@@ -505,6 +614,7 @@ int focus_step(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32_t *s
   ctx->n_timed = 0;
   static const focus_step_out none{};
   const focus_step_out &o = out ? *out : none;
+  RouteScope route_scope(ctx, o.route_experts, o.route_weights);
   const int B = g.block_size, e = g.evict_layer, T0 = n_seq * B;
   const int qkv_w = (g.n_q_heads + 2 * g.n_kv_heads) * g.head_dim, q_w = g.n_q_heads * g.head_dim;
   fk::SlotState st = ctx->slots();
@@ -633,6 +743,7 @@ int focus_run_layers(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int3
   const int qkv_w = (g.n_q_heads + 2 * g.n_kv_heads) * g.head_dim;
   int32_t *cu = ctx->at<int32_t>(pl.off_cu), *row_map = ctx->at<int32_t>(pl.off_row_map), *total = ctx->at<int32_t>(pl.off_total);
   float *resid_p = ctx->at<float>(pl.off_resid_p);
+  RouteScope route_scope(ctx, nullptr, nullptr);
   fk::scan_compact(s, n_seq, B, keep_bits, cu, row_map, total);
   HIP_TRY(ctx, hipMemcpyAsync(resid_p, hidden, (size_t)cap * g.hidden * 4, hipMemcpyDeviceToDevice, s));
   RowSet packed{{cap, total}, {row_map, seq_slot, B}, n_seq, cu, B, nullptr};
@@ -671,6 +782,13 @@ int focus_finalize_blocks(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const
   }
   fk::finalize_advance(s, n_seq, B, seq_slot, st, done, g.mask_token_id);
   HIP_TRY(ctx, hipGetLastError());
+  return FOCUS_OK;
+}
+
+int focus_set_route_override(focus_ctx *ctx, const int32_t *experts) {
+  if (!ctx) return fail(nullptr, FOCUS_EINVAL, "null context");
+  if (experts && ctx->cfg.n_experts == 0) return fail(ctx, FOCUS_EINVAL, "the model has no mixture-of-experts layers");
+  ctx->route_override = experts;
   return FOCUS_OK;
 }
 

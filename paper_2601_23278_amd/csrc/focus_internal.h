@@ -149,6 +149,41 @@ void scan_compact(hipStream_t s, int n_seq, int B, const uint64_t *keep_bits, in
 void gather_rows(hipStream_t s, int dtype, Rows rows, const int32_t *row_map, int B, const int32_t *src_cu, const uint64_t *src_bits,
                  const float *resid, float *resid_p, int hidden, const void *qkv, int qkv_stride, void *q_p, int q_width);
 void silu_mul(hipStream_t s, int dtype, const void *gate_up, void *act, int ffn, Rows rows);
+
+// Mixture-of-experts feed-forward on normalised rows (token-choice routing: every row goes through its k best experts
+// of E, each a SwiGLU feed-forward of inner width Fe; the outputs are mixed with the renormalised router probabilities).
+// Work buffers, all in the workspace; "entry" i = row * k + j is the j-th expert choice of a row.
+constexpr int kMoeTileRows = 128;     // rows of one expert that a workgroup of the grouped projections takes
+struct MoeArgs {
+  int dtype, n_experts, k, expert_ffn, hidden;
+  float route_scale;
+  Rows rows;
+  const int32_t *row_map;             // row -> row id b * B + p (names the row in route_override and in the outputs)
+  const void *u;                      // [rows, hidden] normalised rows
+  const float *logits;                // [rows, E] router logits
+  const int32_t *route_override;      // [row ids, k] experts to use instead of the router's pick, or null
+  int32_t *topk_idx;                  // [rows * k (+4)] expert of every entry
+  float *topk_w;                      // [rows * k] mixing weight of every entry
+  int32_t *list;                      // [E, rows.cap] entries of every expert
+  int32_t *count;                     // [E]
+  int32_t *offs;                      // [E + 1] first expert-sorted row of every expert
+  int32_t *tile_e, *tile_m0;          // [n_tile_slots] row tiles of the grouped projections: expert and first row inside it
+  int32_t *n_tiles;                   // [1]
+  int n_tile_slots;                   // host bound: rows.cap * k / kMoeTileRows + E
+  int32_t *pos;                       // [rows * k] entry -> expert-sorted row
+  int32_t *arow;                      // [rows * k] expert-sorted row -> row of u
+  int32_t *aexp;                      // [rows * k] expert-sorted row -> expert
+  const void *w_gate_up, *w_down;     // [E, 2 Fe, hidden], [E, hidden, Fe]
+  void *act;                          // [rows * k, Fe] expert-sorted rows
+  float *y;                           // [rows * k, hidden] expert outputs, expert-sorted rows
+  float *resid;                       // [rows, hidden] += sum_j weight_j * y[pos[row * k + j]]
+  int32_t *out_experts;               // optional outputs [row ids, k]
+  float *out_weights;
+};
+void moe_route(hipStream_t s, const MoeArgs &a);      // picks and weights
+void moe_group(hipStream_t s, const MoeArgs &a);      // entries sorted by expert, tile list
+void moe_experts(hipStream_t s, const MoeArgs &a);    // the two grouped projections
+void moe_combine(hipStream_t s, const MoeArgs &a);    // weighted sum into the residual stream
 void confidence(hipStream_t s, const float *logits, int vocab, Rows rows, float *conf, int32_t *argmax);
 struct CommitArgs {
   int n_seq, B;

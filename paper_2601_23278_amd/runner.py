@@ -24,6 +24,8 @@ def config_from_workload(wl: Workload, max_batch: int, max_prefix_len: int, n_pa
     c.constraints, c.conf_threshold = wl.constraints, wl.conf_threshold
     c.intra_block_cache = wl.intra_block_cache
     c.selection, c.selection_seed = wl.selection, wl.selection_seed
+    c.n_experts, c.experts_per_token, c.expert_ffn = wl.n_experts, wl.experts_per_token, wl.expert_ffn
+    c.shared_ffn, c.first_moe_layer, c.route_scale = wl.shared_ffn, wl.first_moe_layer, wl.route_scale
     return c
 
 
@@ -67,7 +69,10 @@ def open_session(wl: Workload, device="cuda:0", seq_ids: Optional[Sequence[int]]
     embed, lm_head, norm = wl.embed(dev), wl.lm_head(dev), wl.norm_weight(dev)
     layers = []
     for l in range(wl.n_layers):
-        w = {k: wl.layer_weight(l, k, dev) for k in ("w_qkv", "w_o", "w_gate_up", "w_down")}
+        moe = wl.is_moe_layer(l)
+        w = {k: wl.layer_weight(l, k, dev) for k in (("w_qkv", "w_o") if moe else ("w_qkv", "w_o", "w_gate_up", "w_down"))}
+        if moe:
+            w.update({k: wl.moe_weight(l, k, dev) for k in wl.moe_weight_shapes()})
         w["attn_norm"], w["mlp_norm"] = norm, norm
         layers.append(w)
     pool = torch.empty((wl.n_layers, n_pages, 2, wl.n_kv_heads, wl.page_size, wl.head_dim), dtype=wl.torch_dtype, device=dev)

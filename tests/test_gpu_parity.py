@@ -60,6 +60,10 @@ class Outs:
                       keep_bits=z(n, dt=torch.int64), cu_seqlens=z(n + 1, dt=torch.int32), row_map=z(n * B, dt=torch.int32),
                       conf=z(n * B), argmax=z(n * B, dt=torch.int32), hidden_full=z(n * B, h), hidden_packed=z(n * B, h),
                       logits=z(n * B, V))
+        if wl.n_experts:
+            k = wl.experts_per_token
+            self.t["route_experts"] = torch.full((wl.n_layers, n * B, k), -1, dtype=torch.int32, device=d)
+            self.t["route_weights"] = z(wl.n_layers, n * B, k)
         self.struct = pk.make_step_out(**self.t)
 
     def host(self):
@@ -86,26 +90,51 @@ def check_selection_valid(dI_ora, masked, keep_gpu, K, B, tol):
             assert dI_ora[j] <= kth + tol, (j, dI_ora[j], kth)
 
 
-def compare_steps(wl, steps, tol, exact, seq_ids=None, k_override=None):
+def check_routes(wl, g, tr, tol, exact):
+    """Experts and mixing weights of every row that ran in a mixture-of-experts layer."""
+    for l, rows in tr.route.items():
+        for rid, (experts, weights, logits) in rows.items():
+            got_e = [int(x) for x in g["route_experts"][l, rid]]
+            got_w = g["route_weights"][l, rid].astype(np.float64)
+            if exact:
+                assert got_e == experts, (l, rid, got_e, experts)
+            else:
+                assert got_e == experts, (l, rid)          # forced routing: the given list in its order
+            assert np.max(np.abs(got_w - np.asarray(weights))) <= tol * max(1.0, wl.route_scale), (l, rid, got_w, weights)
+    ran = {l: set(rows) for l, rows in tr.route.items()}
+    for l in range(wl.n_layers):                           # rows that did not run in a layer are left untouched
+        idle = [r for r in range(g["route_experts"].shape[1]) if r not in ran.get(l, ())]
+        assert np.all(g["route_experts"][l, idle] == -1), l
+
+
+def compare_steps(wl, steps, tol, exact, seq_ids=None, k_override=None, forced_routes=False):
     pk, runner = _pk()
     cfg, W, pool, states, lens, tables, n_pages = oracle_batch(wl, seq_ids)
     sess = runner.open_session(wl, DEV, seq_ids)
     n, B = len(states), wl.block_size
     outs = Outs(pk, wl, n)
+    routes = None
+    if forced_routes:
+        routes = wl.route_override(n)
+        sess.focus.focus_set_route_override(torch.tensor(routes, dtype=torch.int32, device=DEV))
     ko_dev = None if k_override is None else torch.tensor(k_override, dtype=torch.int32, device=DEV)
     stats = []
     for step in range(steps):
         print("step", step, flush=True)
         masked_before = [list(st.masked) for st in states]
+        if wl.n_experts:
+            outs.t["route_experts"].fill_(-1)
         sess.focus.focus_step(n, k_override=ko_dev, out=outs.struct)
         g = outs.host()
         keep_gpu = [positions_of(u64(g["keep_bits"][b]), B) for b in range(n)]
         if exact:
             tr = fo.focus_step(cfg, W, pool, states, k_override=k_override,
                                score_cast=lambda d: d.astype(np.float32).astype(np.float64),
-                               conf_cast=lambda c: c.astype(np.float32).astype(np.float64))
+                               conf_cast=lambda c: c.astype(np.float32).astype(np.float64), route_override=routes)
         else:
-            tr = fo.focus_step(cfg, W, pool, states, keep_override=keep_gpu)
+            tr = fo.focus_step(cfg, W, pool, states, keep_override=keep_gpu, route_override=routes)
+        if wl.n_experts:
+            check_routes(wl, g, tr, tol, exact)
         # scores
         e_dI = max(relerr(g["delta_I"][b], tr.delta_I[b]) for b in range(n))
         e_I = max(relerr(g["importance"][b], tr.I_evict[b]) for b in range(n))
@@ -236,6 +265,23 @@ def test_c1_intra_block_cache_with_constraints_and_dynamic_budget():
     assert stats[-1]["frozen"] > 0, stats
 
 
+MOE_TINY = dict(n_experts=8, experts_per_token=2, expert_ffn=64, shared_ffn=32, route_scale=2.5)
+
+
+@pytest.mark.parametrize("first,forced", [(0, False), (1, False), (0, True)])
+def test_c1_moe_fp32_exact(first, forced):
+    """Mixture-of-experts feed-forward (second model of Sec. 5.1) on the tiny fp32 configuration: the router's own picks
+    must equal the oracle's, layer by layer and row by row; with forced routing the given experts are used."""
+    wl = fi.workload("c1_tiny", n_layers=3, first_moe_layer=first, steps=3, **MOE_TINY)
+    compare_steps(wl, wl.steps, 1e-3, exact=True, forced_routes=forced)
+
+
+def test_c1_moe_single_choice_without_shared_expert_and_intra_block_cache():
+    wl = fi.workload("c1_tiny", n_layers=3, n_experts=5, experts_per_token=1, expert_ffn=40, first_moe_layer=1,
+                     intra_block_cache=1, conf_threshold=0.0013, keep_ratio=0.5, steps=5)
+    compare_steps(wl, wl.steps, 1e-3, exact=True)
+
+
 def small_bf16(**over):
     base = dict(n_layers=3, hidden=512, n_q_heads=8, n_kv_heads=2, ffn=1024, vocab=4096, mask_token_id=4095,
                 batch=5, prefix_lo=70, prefix_hi=200, prefix_dist="uniform", block_size=32, budget_mode=1,
@@ -251,6 +297,51 @@ def test_small_bf16_teacher_forced():
 def test_small_bf16_intra_block_cache_teacher_forced():
     stats = compare_steps(small_bf16(intra_block_cache=1, conf_threshold=0.0004, keep_ratio=0.5, steps=6), 6, 2e-2, exact=False)
     assert stats[-1]["frozen"] > 0, stats
+
+
+MOE_SMALL = dict(n_experts=16, experts_per_token=4, expert_ffn=128, shared_ffn=128, route_scale=1.5)
+
+
+@pytest.mark.parametrize("first", [0, 1])
+def test_small_bf16_moe_forced_routes_teacher_forced(first):
+    """bf16 model on the matrix-core grouped projections; both sides use the same seeded routing (a bf16 router logit can
+    flip a near-tie against the float64 oracle, so the pick itself is checked separately below)."""
+    compare_steps(small_bf16(first_moe_layer=first, **MOE_SMALL), 3, 2e-2, exact=False, forced_routes=True)
+
+
+def test_small_bf16_moe_several_row_tiles_per_expert():
+    """Few experts and many rows: an expert's rows span two tiles of the grouped projections, the second one ragged."""
+    wl = small_bf16(batch=12, n_experts=4, experts_per_token=2, expert_ffn=192, shared_ffn=0, first_moe_layer=0, steps=2)
+    compare_steps(wl, 2, 2e-2, exact=False, forced_routes=True)
+
+
+def test_small_bf16_moe_router_picks_are_valid_for_the_oracle_logits():
+    """Free routing in bf16: the oracle is run with the GPU's picks; every pick must be among the oracle's k best experts
+    up to the tolerance on the logits, in descending order up to that tolerance, and the weights must agree."""
+    pk, runner = _pk()
+    wl = small_bf16(first_moe_layer=0, steps=1, **MOE_SMALL)
+    cfg, W, pool, states, lens, tables, n_pages = oracle_batch(wl)
+    sess = runner.open_session(wl, DEV)
+    n, B, k = len(states), wl.block_size, wl.experts_per_token
+    outs = Outs(pk, wl, n)
+    sess.focus.focus_step(n, out=outs.struct)
+    g = outs.host()
+    keep_gpu = [positions_of(u64(g["keep_bits"][b]), B) for b in range(n)]
+    routes = [[[int(x) for x in g["route_experts"][l, r]] for r in range(n * B)] for l in range(wl.n_layers)]
+    tr = fo.focus_step(cfg, W, pool, states, keep_override=keep_gpu, route_override=routes)
+    seen = 0
+    for l, rows in tr.route.items():
+        for rid, (experts, weights, logits) in rows.items():
+            assert len(set(experts)) == k and all(0 <= e < wl.n_experts for e in experts)
+            tol = 2e-2 * max(1.0, float(np.max(np.abs(logits))))
+            kth = np.sort(logits)[-k]
+            assert all(logits[e] >= kth - tol for e in experts), (l, rid)
+            assert all(logits[a] >= logits[b] - tol for a, b in zip(experts, experts[1:])), (l, rid)
+            assert np.max(np.abs(g["route_weights"][l, rid] - np.asarray(weights))) <= 2e-2 * wl.route_scale
+            seen += 1
+    assert seen >= n * B
+    assert relerr(g["hidden_packed"][:tr.cu[-1]], tr.hidden_packed) <= 2e-2
+    sess.focus.focus_free()
 
 
 def test_small_bf16_block64_override_empty_and_full():

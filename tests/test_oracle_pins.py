@@ -848,7 +848,7 @@ def test_moe_ffn_against_masked_dense_formulation_in_torch(E, k, Fs):
     cfg = tiny_cfg(n_experts=E, experts_per_token=k, expert_ffn=12, shared_ffn=Fs, route_scale=1.7)
     w = moe_weights(cfg, r)
     u = r.normal(size=(9, cfg.hidden))
-    y, experts, weights = fo.moe_ffn(cfg, w, u)
+    y, experts, weights, _ = fo.moe_ffn(cfg, w, u)
     tu = torch.from_numpy(u)
     probs = torch.softmax(tu @ torch.from_numpy(w["w_router"]).T, dim=-1)
     val, idx = torch.topk(probs, k, dim=-1)
@@ -869,7 +869,7 @@ def test_moe_forced_routing_uses_the_given_experts():
     w = moe_weights(cfg, r)
     u = r.normal(size=(4, cfg.hidden))
     forced = [[4, 0], [1, 2], [3, 4], [0, 1]]
-    y, experts, weights = fo.moe_ffn(cfg, w, u, forced)
+    y, experts, weights, _ = fo.moe_ffn(cfg, w, u, forced)
     assert experts == forced
     p = torch.softmax(torch.from_numpy(u @ w["w_router"].T), dim=-1).numpy()
     for i in range(4):
