@@ -35,11 +35,20 @@ def gemm_flops_per_step(wl, T0: int, Tp: int) -> float:
     h, F, V = wl.hidden, wl.ffn, wl.vocab
     qkv = (wl.n_q_heads + 2 * wl.n_kv_heads) * wl.head_dim
     qd = wl.n_q_heads * wl.head_dim
-    rest = qd * h + 2 * F * h + F * h                 # O, gate/up, down
+
+    def ffn(l):        # dense feed-forward, or router + shared expert of a mixture-of-experts layer (the routed experts are counted apart)
+        return (wl.n_experts * h + 3 * wl.shared_ffn * h) if wl.is_moe_layer(l) else 3 * F * h
     e = wl.evict_layer
-    full = e * (qkv * h + rest) + qkv * h             # layers < e complete, layer e's QKV
-    packed = rest + (wl.n_layers - e - 1) * (qkv * h + rest) + V * h
+    full = sum(qkv * h + qd * h + ffn(l) for l in range(e)) + qkv * h          # layers < e complete, layer e's QKV
+    packed = qd * h + ffn(e) + sum(qkv * h + qd * h + ffn(l) for l in range(e + 1, wl.n_layers)) + V * h
     return 2.0 * (T0 * full + Tp * packed)
+
+
+def expert_bytes_per_step(wl) -> float:
+    """Weights of the routed experts, read once per mixture-of-experts layer and step (every expert has rows at these batch
+    sizes); activations are not counted."""
+    n_moe = sum(1 for l in range(wl.n_layers) if wl.is_moe_layer(l))
+    return float(n_moe) * wl.n_experts * 3 * wl.hidden * wl.expert_ffn * 2
 
 
 def kv_bytes_per_step(wl, lens) -> float:
@@ -182,6 +191,16 @@ def main():
     roofline = dict(bound="mfma", kernel="gemm (all dense projections of a step)", achieved=round(achieved, 2), peak=PEAK_BF16_TFLOPS,
                     unit="TFLOP/s", frac=round(achieved / PEAK_BF16_TFLOPS, 4), traffic=traffic,
                     flops_per_step=flops, launches=classes["gemm"]["launches"], avg_launch_ms=round(gemm_ms / max(1, classes["gemm"]["launches"]), 5))
+    dense_gemm = None
+    if wl.n_experts:
+        # mixture-of-experts model: the grouped expert projections stream the expert weights once per layer and dominate
+        dense_gemm = roofline
+        ex_ms, ex_n = classes["experts"]["ms"], classes["experts"]["launches"]
+        eb = expert_bytes_per_step(wl)
+        gbs = eb / (ex_ms * 1e-3) / 1e9 if ex_ms > 0 else 0.0
+        roofline = dict(bound="hbm", kernel="grouped expert projections (gate/up + down of every mixture-of-experts layer)",
+                        achieved=round(gbs, 1), peak=PEAK_HBM_GBS, unit="GB/s", frac=round(gbs / PEAK_HBM_GBS, 4), traffic=None,
+                        bytes_per_step=eb, launches=ex_n, avg_launch_ms=round(ex_ms / max(1, ex_n), 5))
     attention = dict(bound="hbm", achieved=round(kvb / (attn_ms * 1e-3) / 1e9, 1) if attn_ms > 0 else 0.0, peak=PEAK_HBM_GBS, unit="GB/s",
                      frac=round(kvb / (attn_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4) if attn_ms > 0 else 0.0, kv_bytes_per_step=kvb)
 
@@ -203,15 +222,17 @@ def main():
 
     sess.focus.focus_free()
     line = {
-        "metric": "decoded tokens/s at batch %d (8B-shaped, bf16, 1 GPU)" % n, "value": round(head["decoded_tokens_per_s"], 2),
+        "metric": "decoded tokens/s at batch %d (%s, bf16, 1 GPU)" % (n, "8B-shaped" if not wl.n_experts else "mixture-of-experts, 16B total / 1.4B active shape"), "value": round(head["decoded_tokens_per_s"], 2),
         "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(head["ms_per_step"], 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": "%s: %d layers, hidden %d, %dq/%dkv x %d, ffn %d, vocab %d, batch %d, prefix %s[%d,%d], block %d, keep ratio %.3f"
                                % (wl.name, wl.n_layers, wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, wl.vocab, n,
                                   wl.prefix_dist, wl.prefix_lo, wl.prefix_hi, B, args.keep_ratio),
                    "rows_full": n * B, "rows_packed": head["rows_packed"], "decoded_per_step": head["decoded_per_step"],
+                   "experts": None if not wl.n_experts else "%d experts x %d, %d per token, shared %d, dense below layer %d"
+                              % (wl.n_experts, wl.expert_ffn, wl.experts_per_token, wl.shared_ffn, wl.first_moe_layer),
                    "debug_overrides": {k: v for k, v in (("layers", args.layers), ("batch", args.batch)) if v}},
-        "roofline": roofline, "attention_hbm": attention, "kernel_classes_ms": classes, "cpu_baseline": cpu, "sweep": sweep,
+        "roofline": roofline, "dense_gemm": dense_gemm, "attention_hbm": attention, "kernel_classes_ms": classes, "cpu_baseline": cpu, "sweep": sweep,
         "setup_s": round(t_setup, 1),
     }
     print(json.dumps(line))

@@ -233,10 +233,9 @@ class Workload:
         return shapes
 
     def moe_weight(self, layer: int, which: str, device="cpu") -> torch.Tensor:
-        """Router rows are drawn with a larger spread (std 0.1) so that the routing probabilities are well apart."""
         order = {"w_router": 0, "w_expert_gate_up": 1, "w_expert_down": 2, "w_shared_gate_up": 3, "w_shared_down": 4}
         out = torch.empty(self.moe_weight_shapes()[which], dtype=self.torch_dtype, device=device)
-        return fill_normal_(out, self.seed, TID_MOE0 + 8 * layer + order[which], 0.1 if which == "w_router" else WEIGHT_STD)
+        return fill_normal_(out, self.seed, TID_MOE0 + 8 * layer + order[which], WEIGHT_STD)
 
     def route_override(self, n_seq: Optional[int] = None) -> List[List[List[int]]]:
         """Seeded forced routing [layer][row id b * B + p] -> experts_per_token distinct experts (teacher forcing)."""
@@ -309,6 +308,16 @@ _add(Workload(name="c4_batch256", seed=3, n_layers=36, block_size=32, batch=256,
 # configs[4]: batch 64, prefix log-uniform [1024,32768], paged (64) with shuffled pages, B=64, per-seq K.
 _add(Workload(name="c5_ragged", seed=4, n_layers=36, block_size=64, batch=64, prefix_lo=1024, prefix_hi=32768,
               prefix_dist="loguniform", budget_mode=3, keep_ratio=0.25, steps=1, shuffle_pages=True, **_SHAPE_8B))
+
+
+# Second workload (Sec. 5.1): a mixture-of-experts model with the parameter counts the paper states for it, 16B in
+# total and 1.4B active per token: 20 layers, hidden 2048, 256 experts of inner width 512 with 8 active plus one shared
+# expert, a dense first layer; same batch recipe as the batch-256 configuration.
+_add(Workload(name="c6_moe_mini", seed=5, n_layers=20, hidden=2048, n_q_heads=16, n_kv_heads=4, head_dim=128, ffn=5120,
+              vocab=157184, dtype="bf16", rope_base=6.0e5, rms_eps=1e-6, mask_token_id=157183, page_size=64,
+              prefill="synthetic", block_size=32, batch=256, prefix_lo=512, prefix_hi=4096, prefix_dist="uniform",
+              budget_mode=1, keep_ratio=0.25, steps=1, n_experts=256, experts_per_token=8, expert_ffn=512, shared_ffn=512,
+              first_moe_layer=1, route_scale=2.5))
 
 
 def workload(name: str, **overrides) -> Workload:

@@ -240,8 +240,10 @@ enum { FOCUS_KC_GEMM = 0,      /* dense projections: QKV, O, gate/up, down, lm_h
        FOCUS_KC_EVICT = 2,     /* importance, budget + selection, scan, gather */
        FOCUS_KC_POINTWISE = 3, /* embedding, RMSNorm, rotary + K/V write, SiLU*up */
        FOCUS_KC_DECODE = 4,    /* confidence over the vocabulary, commit */
-       FOCUS_KC_ROUTE = 5,     /* mixture-of-experts: picks, sorting by expert, weighted sum (the expert projections are GEMM) */
-       FOCUS_KC_COUNT = 6 };
+       FOCUS_KC_ROUTE = 5,     /* mixture-of-experts: picks, sorting by expert, weighted sum */
+       FOCUS_KC_EXPERTS = 6,   /* mixture-of-experts: the grouped gate/up and down projections of the routed experts
+                                  (router and shared expert are dense projections, FOCUS_KC_GEMM) */
+       FOCUS_KC_COUNT = 7 };
 int focus_set_timing(focus_ctx *ctx, int32_t enable);
 int focus_get_kernel_time(focus_ctx *ctx, int32_t kernel_class, float *total_ms, int32_t *launches);
 

@@ -18,8 +18,8 @@ LIB_PATH = os.path.join(_HERE, "libfocus.so")
 FOCUS_OK, FOCUS_EINVAL, FOCUS_ENOMEM, FOCUS_EHIP = 0, -1, -2, -3
 FOCUS_F32, FOCUS_BF16 = 0, 1
 FOCUS_MAX_BLOCK = 64
-KC_GEMM, KC_ATTENTION, KC_EVICT, KC_POINTWISE, KC_DECODE, KC_ROUTE, KC_COUNT = 0, 1, 2, 3, 4, 5, 6
-KC_NAMES = ["gemm", "attention", "evict", "pointwise", "decode", "route"]
+KC_GEMM, KC_ATTENTION, KC_EVICT, KC_POINTWISE, KC_DECODE, KC_ROUTE, KC_EXPERTS, KC_COUNT = 0, 1, 2, 3, 4, 5, 6, 7
+KC_NAMES = ["gemm", "attention", "evict", "pointwise", "decode", "route", "experts"]
 
 
 class focus_config(C.Structure):

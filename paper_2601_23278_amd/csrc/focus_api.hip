@@ -319,7 +319,7 @@ void moe_ffn(focus_ctx *c, hipStream_t s, int l, const RowSet &rs, float *resid,
   { Timed t(c, s, FOCUS_KC_GEMM);
     fk::gemm(s, g.dtype, normed, c->w_router[l], g.n_experts, g.hidden, rs.rows, fk::EPI_STORE_F32, c->at<float>(pl.off_moe_logits), g.n_experts); }
   { Timed t(c, s, FOCUS_KC_ROUTE); fk::moe_route(s, a); fk::moe_group(s, a); }
-  { Timed t(c, s, FOCUS_KC_GEMM); fk::moe_experts(s, a); }
+  { Timed t(c, s, FOCUS_KC_EXPERTS); fk::moe_experts(s, a); }
   // the shared expert adds into the residual stream before the routed sum (both orders are the same sum)
   if (g.shared_ffn > 0) swiglu_ffn(c, s, rs, normed, c->w_shared_gate_up[l], c->w_shared_down[l], g.shared_ffn, resid, fk::Warm());
   { Timed t(c, s, FOCUS_KC_ROUTE); fk::moe_combine(s, a); }

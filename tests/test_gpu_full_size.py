@@ -35,11 +35,28 @@ def run_full_and_compare(wl, sample_ids, k_override=None):
              importance=z(n, B), delta_I=z(n, B), K=z(n, dt=torch.int32), keep_bits=z(n, dt=torch.int64),
              cu_seqlens=z(n + 1, dt=torch.int32), row_map=z(n * B, dt=torch.int32), conf=z(n * B),
              argmax=z(n * B, dt=torch.int32), hidden_full=z(n * B, h), hidden_packed=z(n * B, h), logits=z(n * B, V))
+    if wl.n_experts:
+        t["route_experts"] = torch.full((wl.n_layers, n * B, wl.experts_per_token), -1, dtype=torch.int32, device=DEV)
+        t["route_weights"] = z(wl.n_layers, n * B, wl.experts_per_token)
     ko = None if k_override is None else torch.tensor(k_override, dtype=torch.int32, device=DEV)
     print("gpu step", flush=True)
     sess.focus.focus_step(n, k_override=ko, out=pk.make_step_out(**t))
     torch.cuda.synchronize()
     small = {k: v.cpu().numpy() for k, v in t.items() if k != "logits" and not k.startswith("hidden")}
+    routes = None
+    if wl.n_experts:
+        # every row of a mixture-of-experts layer got k distinct experts and weights that sum to route_scale
+        re_, rw = small["route_experts"], small["route_weights"]
+        for l in range(wl.n_layers):
+            ran = re_[l][:, 0] >= 0
+            assert ran.sum() == (0 if not wl.is_moe_layer(l) else (n * B if l < wl.evict_layer else int(small["cu_seqlens"][-1]))), l
+            if ran.any():
+                srt = np.sort(re_[l][ran], axis=1)
+                assert np.all(srt[:, 1:] > srt[:, :-1]) and srt.min() >= 0 and srt.max() < wl.n_experts
+                assert np.allclose(rw[l][ran].sum(axis=1), wl.route_scale, rtol=1e-4)
+                assert np.all(rw[l][ran][:, :-1] >= rw[l][ran][:, 1:])
+        # the oracle is teacher-forced with the picks of the sampled sequences (checked against its own logits below)
+        routes = [[[int(x) for x in re_[l, b * B + p]] for b in sample_ids for p in range(B)] for l in range(wl.n_layers)]
     cu = [int(x) for x in small["cu_seqlens"]]
     keep = [positions_of(u64(small["keep_bits"][b]), B) for b in range(n)]
     # properties over the whole batch
@@ -67,8 +84,15 @@ def run_full_and_compare(wl, sample_ids, k_override=None):
     L = wl.n_layers
     windows = [l for l in sorted({2, L // 2, L - 2}) if l > wl.evict_layer and l + 2 <= L]
     rec = set(windows) | {l + 2 for l in windows}
-    tr = fo.focus_step(cfg, W, pool, states, keep_override=[keep[b] for b in sample_ids], record_layers=rec)
+    tr = fo.focus_step(cfg, W, pool, states, keep_override=[keep[b] for b in sample_ids], record_layers=rec, route_override=routes)
     TOLE = drift_tol(L)
+    for l, rows in tr.route.items():
+        for rid, (experts, weights, logits) in rows.items():
+            tol = TOLE * max(1.0, float(np.max(np.abs(logits))))
+            kth = np.sort(logits)[-wl.experts_per_token]
+            assert all(logits[x] >= kth - tol for x in experts), (l, rid)
+            grid = sample_ids[rid // B] * B + rid % B
+            assert np.max(np.abs(small["route_weights"][l, grid] - np.asarray(weights))) <= 2 * TOLE * wl.route_scale, (l, rid)
     for i, b in enumerate(sample_ids):
         assert relerr(small["importance"][b], tr.I_evict[i]) <= TOL
         scale = float(np.max(np.abs(tr.delta_I[i])))
@@ -98,6 +122,11 @@ def run_full_and_compare(wl, sample_ids, k_override=None):
         kb = torch.tensor([bits_of(keep[b]) - (1 << 64) if bits_of(keep[b]) >= (1 << 63) else bits_of(keep[b]) for b in sample_ids],
                           dtype=torch.int64, device=DEV)
         slots = torch.tensor(sample_ids, dtype=torch.int32, device=DEV)
+        if wl.n_experts:             # the windows use the step's picks (rows are named by their place in the window's batch)
+            forced = torch.zeros_like(t["route_experts"])
+            for i, b in enumerate(sample_ids):
+                forced[:, i * B:(i + 1) * B] = t["route_experts"][:, b * B:(b + 1) * B]
+            sess.focus.focus_set_route_override(forced)
         for l in windows:
             hid = torch.zeros(ns * B, h, device=DEV)
             hid[:Tp] = torch.from_numpy(tr.hidden_entering[l]).to(DEV, torch.float32)
@@ -125,3 +154,11 @@ def test_c5_ragged_long_context_paged():
     ks = wl.k_overrides()
     lens = wl.prefix_lens()
     run_full_and_compare(wl, [0, 1, int(np.argmax(lens))], k_override=ks)
+
+
+def test_c6_moe_mini_full_size_batch_and_expert_shapes():
+    """Second workload (mixture-of-experts, 256 experts of which 8 per token, one shared expert, dense first layer) at its
+    full batch, lengths and expert shapes; the layer count is cut to 4 to bound the oracle's time.  Routing runs free on
+    the GPU; the oracle is teacher-forced with the picks of the sampled sequence after checking them against its logits."""
+    wl = fi.workload("c6_moe_mini", n_layers=4)
+    run_full_and_compare(wl, [int(np.argmin(wl.prefix_lens()))])
