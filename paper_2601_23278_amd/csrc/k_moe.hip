@@ -3,9 +3,9 @@
 // weighted sum back into the residual stream.
 //
 // With k of E experts per row and a few thousand rows per step an expert sees a few dozen rows, so the grouped
-// projections are bound by streaming the expert weights from HBM once, not by the matrix cores: the kernel keeps three
-// K-slabs of weights in flight per workgroup (four LDS stages filled by direct-to-LDS loads) and the matrix work hides
-// underneath.  Everything is deterministic: entries are placed by prefix sums, never by atomics, and a row's result
+// projections are bound by streaming the expert weights from HBM once, not by the matrix cores: the kernel keeps two
+// K-slabs of weights in flight per workgroup and two workgroups per CU (LDS stages filled by direct-to-LDS loads), and
+// the matrix work hides underneath.  Everything is deterministic: entries are placed by prefix sums, never by atomics, and a row's result
 // does not depend on which other rows share its tile.
 #include <algorithm>
 
@@ -156,9 +156,11 @@ void moe_group(hipStream_t s, const MoeArgs &a) {
 // ---------------------------------------------------------------------------------------------
 // Grouped projection on the matrix cores: out[row] = A[src(row)] * W[expert(row)]^T for the expert-sorted rows.
 // A workgroup (4 wavefronts, 2 x 2, each 64 x 64) takes one tile of up to 128 rows of one expert and 128 rows of that
-// expert's weight matrix; K-slabs of 64 go straight into LDS (buffer_load_dwordx4 ... lds, chunk-swizzled like the dense
-// kernel), four stages, three slabs in flight.  Rows beyond the expert's count and weight rows beyond N fall outside the
-// buffer descriptors and read as zero.
+// expert's weight matrix, so that with the usual few dozen rows per expert every weight byte is fetched by exactly one
+// workgroup.  K-slabs of 64 go straight into LDS (buffer_load_dwordx4 ... lds, chunk-swizzled like the dense kernel):
+// three stages for the weights (two slabs in flight: they come from HBM), two for the rows (one in flight: they come
+// from the L2), 80 KB in all, so two workgroups share a CU and one streams while the other starts or stores.
+// Rows beyond the expert's count and weight rows beyond N fall outside the buffer descriptors and read as zero.
 //   GATE_UP: W = [Fe gate rows; Fe up rows] per expert; LDS weight rows 64 c .. 64 c + 31 are the gate rows of output
 //            columns 32 c .., the next 32 the matching up rows; out[bf16][row, col] = silu(gate) * up.
 //   else:    out[f32][row, col] = acc.
@@ -176,16 +178,22 @@ struct GroupGemm {
 
 #define FK_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 constexpr int vmcnt_imm(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }   // s_waitcnt vmcnt(n) only
+constexpr int kGroupLds = (2 * kMoeTileRows + 3 * 128) * 128;
 
 template <bool GATE_UP>
-__global__ __launch_bounds__(256, 1) void k_group_gemm(GroupGemm g) {
+__global__ __launch_bounds__(256, 2) void k_group_gemm(GroupGemm g) {
 #if defined(__HIP_DEVICE_COMPILE__)   // buffer-resource builtins exist in the device pass only
-  constexpr int BM = kMoeTileRows, BN = 128, STAGES = 4, ASTAGE = BM * 128, STAGE = (BM + BN) * 128;
-  constexpr int IA = BM / 8 / 4, IB = BN / 8 / 4, NI = IA + IB;   // load instructions per wavefront and slab
+  constexpr int BM = kMoeTileRows, BN = 128, ASTAGE = BM * 128, WSTAGE = BN * 128, WBASE = 2 * ASTAGE;
+  constexpr int IA = BM / 8 / 4, IB = BN / 8 / 4;   // load instructions per wavefront and slab
+  static_assert(BM == 128, "wavefront layout below is 2 x 2 of 64 x 64");
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds_group[];
   unsigned char *const lds = lds_group;
-  const int t = blockIdx.x / g.tiles_n, nt = blockIdx.x % g.tiles_n;
-  if (t >= *g.n_tiles) return;
+  // work item = weight tile nt of row tile t, nt fastest; XCD x (workgroups x, x + 8, ...) takes a contiguous range, so
+  // the workgroups that read the same rows share an L2
+  const int n_tiles = *g.n_tiles, total = n_tiles * g.tiles_n, per_xcd = (total + 7) / 8;
+  const int item = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  if ((int)(blockIdx.x / 8) >= per_xcd || item >= total) return;
+  const int t = item / g.tiles_n, nt = item % g.tiles_n;
   const int e = g.tile_e[t], m0 = g.tile_m0[t];
   const int row0 = g.offs[e] + m0, valid = min(BM, g.count[e] - m0);
   const int N = g.N, K = g.K, n0 = nt * (GATE_UP ? BN / 2 : BN);
@@ -208,15 +216,18 @@ __global__ __launch_bounds__(256, 1) void k_group_gemm(GroupGemm g) {
     vob[q] = ok ? (unsigned)wrow * (unsigned)K * 2u + c * 16 : 0x80000000u;
   }
   const int nk = K / 64;
-  auto issue = [&](int kt) {   // slab kt into stage kt % STAGES; beyond the last slab the offset is out of range: nothing moves
-    unsigned char *st = lds + (kt & (STAGES - 1)) * STAGE;
+  // slab kt of an operand into a stage; beyond the last slab the offset is out of range: nothing moves
+  auto issue_a = [&](int kt, int stage) {
     const unsigned so = kt < nk ? (unsigned)kt * 128u : 0x80000000u;
 #pragma unroll
     for (int q = 0; q < IA; ++q)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_a, FK_LDS_PTR(st + (wave * IA + q) * 1024), 16, voa[q], so, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_a, FK_LDS_PTR(lds + stage * ASTAGE + (wave * IA + q) * 1024), 16, voa[q], so, 0, 0);
+  };
+  auto issue_w = [&](int kt, int stage) {
+    const unsigned so = kt < nk ? (unsigned)kt * 128u : 0x80000000u;
 #pragma unroll
     for (int q = 0; q < IB; ++q)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, FK_LDS_PTR(st + ASTAGE + (wave * IB + q) * 1024), 16, vob[q], so, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, FK_LDS_PTR(lds + WBASE + stage * WSTAGE + (wave * IB + q) * 1024), 16, vob[q], so, 0, 0);
   };
   f32x16 acc[2][2];
 #pragma unroll
@@ -226,14 +237,17 @@ __global__ __launch_bounds__(256, 1) void k_group_gemm(GroupGemm g) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
   const int frow = lane & 31, fch = lane >> 5, sw = (frow >> 1) & 7;
-  issue(0);
-  issue(1);
-  issue(2);
+  issue_a(0, 0);
+  issue_w(0, 0);
+  issue_w(1, 1);
+  int ws = 0;   // weight stage of slab kt
   for (int kt = 0; kt < nk; ++kt) {
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * NI));   // this wavefront's part of slab kt has landed (two younger slabs may be in flight)
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // ... and everyone's; everyone has finished slab kt - 1
-    issue(kt + 3);                                   // into the stage slab kt - 1 occupied
-    const unsigned char *sa = lds + (kt & (STAGES - 1)) * STAGE, *sb = sa + ASTAGE;
+    // loads are issued in the order ... rows(kt), weights(kt + 1): all but the youngest IB have landed = slab kt is complete
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(IB));
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // ... for every wavefront; and everyone has finished slab kt - 1
+    issue_a(kt + 1, (kt + 1) & 1);                    // into the stages slab kt - 1 occupied
+    issue_w(kt + 2, ws == 0 ? 2 : ws - 1);
+    const unsigned char *sa = lds + (kt & 1) * ASTAGE, *sb = lds + WBASE + ws * WSTAGE;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       bf16x8 fa[2], fb[2];
@@ -247,6 +261,7 @@ __global__ __launch_bounds__(256, 1) void k_group_gemm(GroupGemm g) {
 #pragma unroll
         for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
+    ws = ws == 2 ? 0 : ws + 1;
   }
   __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
   // accumulator register r of lane l is C[8 * (r / 4) + 4 * (l / 32) + r % 4][l % 32] of its 32 x 32 tile
@@ -300,13 +315,13 @@ __global__ __launch_bounds__(256) void k_group_gemm_valu(const T *A, const int32
 
 template <bool GATE_UP>
 static bool launch_group(hipStream_t s, const GroupGemm &g, int n_tile_slots) {
-  constexpr int kLds = 4 * (kMoeTileRows + 128) * 128;
+  constexpr int kLds = kGroupLds;
   static bool ready = false;             // the dynamic LDS size has to be allowed once per kernel
   if (!ready) {
     if (hipFuncSetAttribute((const void *)k_group_gemm<GATE_UP>, hipFuncAttributeMaxDynamicSharedMemorySize, kLds) != hipSuccess) return false;
     ready = true;
   }
-  k_group_gemm<GATE_UP><<<n_tile_slots * g.tiles_n, 256, kLds, s>>>(g);
+  k_group_gemm<GATE_UP><<<((n_tile_slots * g.tiles_n + 7) / 8) * 8, 256, kLds, s>>>(g);
   return true;
 }
 
