@@ -66,7 +66,8 @@ def cpu_baseline(wl, n_seq_sample: int, n_layers_sample: int):
     from oracle.harness import oracle_batch
     import focus_inputs as fi
 
-    small = fi.workload(wl.name, n_layers=n_layers_sample, keep_ratio=wl.keep_ratio, budget_mode=wl.budget_mode)
+    from dataclasses import replace
+    small = replace(wl, n_layers=n_layers_sample)
     cfg, W, pool, states, lens, tables, n_pages = oracle_batch(small, list(range(n_seq_sample)), lazy_embed=True)
     marks = []
     inner = W._layer_fn
@@ -104,7 +105,7 @@ def main():
     ap.add_argument("--steps", type=int, default=8)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="c4_batch256")
-    ap.add_argument("--keep-ratio", type=float, default=0.25)
+    ap.add_argument("--keep-ratio", type=float, default=None, help="fixed-ratio budget (default: the workload's own budget rule)")
     ap.add_argument("--sweep", action="store_true", help="also time keep ratios 1.0, 0.5, 0.125")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debug only; the JSON says so)")
     ap.add_argument("--batch", type=int, default=0, help="override the batch (debug only)")
@@ -124,12 +125,16 @@ def main():
     import paper_2601_23278_amd as pk
     from paper_2601_23278_amd import runner
 
-    over = dict(keep_ratio=args.keep_ratio, budget_mode=1)
+    over = {} if args.keep_ratio is None else dict(keep_ratio=args.keep_ratio, budget_mode=1)
     if args.layers:
         over["n_layers"] = args.layers
     if args.batch:
         over["batch"] = args.batch
     wl = fi.workload(args.workload, **over)
+    if wl.budget_mode not in (0, 1):
+        print("bench.py: workload %s has a per-sequence budget; give --keep-ratio" % wl.name, file=sys.stderr)
+        sys.exit(2)
+    ratio0 = wl.keep_ratio if wl.budget_mode == 1 else wl.topk / wl.block_size      # fraction of the block that is retained
     t_setup = time.time()
     sess = runner.open_session(wl, "cuda:0")
     torch.cuda.synchronize()
@@ -145,9 +150,12 @@ def main():
 
     def run(ratio: float, steps: int, warmup: int):
         """Times `steps` consecutive denoising steps of one block at the given keep ratio."""
-        sess.reopen(keep_ratio=ratio)
+        if wl.budget_mode == 1:
+            sess.reopen(keep_ratio=ratio)
+        else:
+            sess.reopen()
         f = sess.focus
-        K = min(B, max(0, int(math.ceil(float(torch.tensor(ratio, dtype=torch.float32)) * B))))
+        K = min(B, max(0, int(math.ceil(float(torch.tensor(ratio, dtype=torch.float32)) * B)))) if wl.budget_mode == 1 else wl.topk
         period = max(1, B - K) if K < B else B          # steps before a block runs out of masked tokens
         reinstall()
         for _ in range(warmup):
@@ -166,10 +174,10 @@ def main():
         return dict(keep_ratio=ratio, ms_per_step=1e3 * dt / steps, decoded_tokens_per_s=float(decoded.item()) / dt,
                     decoded_per_step=float(decoded.item()) / steps, rows_full=n * B, rows_packed=int(cu[-1].item()))
 
-    head = run(args.keep_ratio, args.steps, args.warmup)
+    head = run(ratio0, args.steps, args.warmup)
 
     # per-class device time of one step (event pairs around every launch; separate pass)
-    sess.reopen(keep_ratio=args.keep_ratio)
+    sess.reopen()
     f = sess.focus
     f.focus_set_timing(True)
     f.focus_step(n, out=out)
@@ -185,7 +193,7 @@ def main():
     kvb = kv_bytes_per_step(wl, sess.prefix_lens)
     attn_ms = classes["attention"]["ms"]
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "pmc_traffic_%s_keep%03d.json" % (wl.name, int(round(1000 * args.keep_ratio))))
+    tpath = os.path.join(ROOT, "profiles", "pmc_traffic_%s_keep%03d.json" % (wl.name, int(round(1000 * ratio0))))
     if os.path.exists(tpath) and not (args.layers or args.batch):
         traffic = json.load(open(tpath)).get("gemm_hbm_bytes_per_step")
     roofline = dict(bound="mfma", kernel="gemm (all dense projections of a step)", achieved=round(achieved, 2), peak=PEAK_BF16_TFLOPS,
@@ -214,7 +222,7 @@ def main():
 
     sweep = None
     if args.sweep:
-        sweep = [head] + [run(r, args.steps, args.warmup) for r in (1.0, 0.5, 0.125) if abs(r - args.keep_ratio) > 1e-9]
+        sweep = [head] + [run(r, args.steps, args.warmup) for r in (1.0, 0.5, 0.125) if abs(r - ratio0) > 1e-9 and wl.budget_mode == 1]
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -227,7 +235,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": "%s: %d layers, hidden %d, %dq/%dkv x %d, ffn %d, vocab %d, batch %d, prefix %s[%d,%d], block %d, keep ratio %.3f"
                                % (wl.name, wl.n_layers, wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, wl.vocab, n,
-                                  wl.prefix_dist, wl.prefix_lo, wl.prefix_hi, B, args.keep_ratio),
+                                  wl.prefix_dist, wl.prefix_lo, wl.prefix_hi, B, ratio0),
                    "rows_full": n * B, "rows_packed": head["rows_packed"], "decoded_per_step": head["decoded_per_step"],
                    "experts": None if not wl.n_experts else "%d experts x %d, %d per token, shared %d, dense below layer %d"
                               % (wl.n_experts, wl.expert_ffn, wl.experts_per_token, wl.shared_ffn, wl.first_moe_layer),

@@ -26,6 +26,7 @@ struct Plan {
   // mixture-of-experts work buffers (zero-sized for a dense model)
   size_t off_moe_logits, off_moe_idx, off_moe_w, off_moe_list, off_moe_count, off_moe_offs, off_moe_tile_e, off_moe_tile_m0,
       off_moe_ntiles, off_moe_pos, off_moe_arow, off_moe_aexp, off_moe_act, off_moe_y;
+  size_t off_splitk, splitk_bytes;   // fp32 partial sums of K-split projections (launches with few rows)
   size_t bytes, part_entries;
   int table_stride, max_rows, max_pos, moe_tile_slots;
 };
@@ -87,6 +88,8 @@ Plan make_plan(const focus_config &c) {
   p.off_order = take(nb * 4);
   p.off_uncached = take(nb * 8);
   p.off_finalized = take(nb * 4);
+  p.splitk_bytes = c.dtype == FOCUS_BF16 ? (size_t)64 << 20 : 0;
+  p.off_splitk = take(p.splitk_bytes);
   if (c.n_experts > 0) {
     const size_t E = c.n_experts, ent = rows * c.experts_per_token;
     p.moe_tile_slots = (int)(ent / fk::kMoeTileRows + E);
@@ -170,6 +173,7 @@ struct focus_ctx {
             at<int64_t>(plan.off_token_sum), at<int32_t>(plan.off_total_steps), cfg.max_batch,
             at<int32_t>(plan.off_page_count), cfg.max_prefix_len, at<uint64_t>(plan.off_cached)};
   }
+  fk::Scratch scratch() const { return fk::Scratch{plan.splitk_bytes ? ws + plan.off_splitk : nullptr, plan.splitk_bytes}; }
   bool moe_layer(int l) const { return cfg.n_experts > 0 && l >= cfg.first_moe_layer; }
   fk::KvLayer kv_layer(int l) const {
     size_t layer_bytes = (size_t)cfg.n_pages * 2 * cfg.n_kv_heads * cfg.page_size * cfg.head_dim * esize(cfg.dtype);
@@ -242,7 +246,7 @@ void layer_qkv(focus_ctx *c, hipStream_t s, int l, const RowSet &rs, const float
   const int qkv_w = (g.n_q_heads + 2 * g.n_kv_heads) * g.head_dim;
   void *normed = c->at<char>(c->plan.off_normed), *qkv = c->at<char>(c->plan.off_qkv);
   { Timed t(c, s, FOCUS_KC_POINTWISE); fk::rmsnorm(s, g.dtype, resid, c->attn_norm[l], normed, g.hidden, g.rms_eps, rs.rows); }
-  { Timed t(c, s, FOCUS_KC_GEMM); fk::gemm(s, g.dtype, normed, c->w_qkv[l], qkv_w, g.hidden, rs.rows, fk::EPI_STORE, qkv, qkv_w); }
+  { Timed t(c, s, FOCUS_KC_GEMM); fk::gemm(s, g.dtype, normed, c->w_qkv[l], qkv_w, g.hidden, rs.rows, fk::EPI_STORE, qkv, qkv_w, fk::Warm(), c->scratch()); }
   { Timed t(c, s, FOCUS_KC_POINTWISE);
     fk::rope_kv_write(s, g.dtype, qkv, g.n_q_heads, rs.rows, rs.ri, c->slots(), c->kv_layer(l), c->at<float2>(c->plan.off_rope), rs.n_seq, rs.cu); }
 }
@@ -269,7 +273,7 @@ void layer_rest(focus_ctx *c, hipStream_t s, int l, const RowSet &rs, float *res
     attention_split(c, rs.n_seq, rs.rows.cap, &a.chunk, &a.launch_splits);
     a.max_splits = a.launch_splits;
     fk::attention(s, a); }
-  { Timed t(c, s, FOCUS_KC_GEMM); fk::gemm(s, g.dtype, attn, c->w_o[l], g.hidden, q_w, rs.rows, fk::EPI_ADD_F32, resid, g.hidden); }
+  { Timed t(c, s, FOCUS_KC_GEMM); fk::gemm(s, g.dtype, attn, c->w_o[l], g.hidden, q_w, rs.rows, fk::EPI_ADD_F32, resid, g.hidden, fk::Warm(), c->scratch()); }
   { Timed t(c, s, FOCUS_KC_POINTWISE); fk::rmsnorm(s, g.dtype, resid, c->mlp_norm[l], normed, g.hidden, g.rms_eps, rs.rows); }
   const size_t qkv_bytes = (size_t)(g.n_q_heads + 2 * g.n_kv_heads) * g.head_dim * g.hidden * esize(g.dtype);
   const fk::Warm next_qkv = l + 1 < g.n_layers ? fk::Warm{c->w_qkv[l + 1], qkv_bytes} : fk::Warm();
@@ -288,12 +292,12 @@ void swiglu_ffn(focus_ctx *c, hipStream_t s, const RowSet &rs, const void *norme
   if (fk::gemm_fuses_silu_mul(g.dtype, normed, w_gate_up, 2 * ffn, g.hidden)) {
     Timed t(c, s, FOCUS_KC_GEMM);
     fk::gemm(s, g.dtype, normed, w_gate_up, 2 * ffn, g.hidden, rs.rows, fk::EPI_SILU_MUL, act, ffn,
-             fk::Warm{w_down, (size_t)g.hidden * ffn * esize(g.dtype)});
+             fk::Warm{w_down, (size_t)g.hidden * ffn * esize(g.dtype)}, c->scratch());
   } else {
-    { Timed t(c, s, FOCUS_KC_GEMM); fk::gemm(s, g.dtype, normed, w_gate_up, 2 * ffn, g.hidden, rs.rows, fk::EPI_STORE, gate_up, 2 * ffn); }
+    { Timed t(c, s, FOCUS_KC_GEMM); fk::gemm(s, g.dtype, normed, w_gate_up, 2 * ffn, g.hidden, rs.rows, fk::EPI_STORE, gate_up, 2 * ffn, fk::Warm(), c->scratch()); }
     { Timed t(c, s, FOCUS_KC_POINTWISE); fk::silu_mul(s, g.dtype, gate_up, act, ffn, rs.rows); }
   }
-  { Timed t(c, s, FOCUS_KC_GEMM); fk::gemm(s, g.dtype, act, w_down, g.hidden, ffn, rs.rows, fk::EPI_ADD_F32, resid, g.hidden, warm_after); }
+  { Timed t(c, s, FOCUS_KC_GEMM); fk::gemm(s, g.dtype, act, w_down, g.hidden, ffn, rs.rows, fk::EPI_ADD_F32, resid, g.hidden, warm_after, c->scratch()); }
 }
 
 // Mixture-of-experts feed-forward on normalised rows, added to the residual stream: router logits -> picks and weights ->
@@ -317,7 +321,7 @@ void moe_ffn(focus_ctx *c, hipStream_t s, int l, const RowSet &rs, float *resid,
   a.out_experts = c->route_by_row_id && c->out_route_experts ? c->out_route_experts + (size_t)l * plane : nullptr;
   a.out_weights = c->route_by_row_id && c->out_route_weights ? c->out_route_weights + (size_t)l * plane : nullptr;
   { Timed t(c, s, FOCUS_KC_GEMM);
-    fk::gemm(s, g.dtype, normed, c->w_router[l], g.n_experts, g.hidden, rs.rows, fk::EPI_STORE_F32, c->at<float>(pl.off_moe_logits), g.n_experts); }
+    fk::gemm(s, g.dtype, normed, c->w_router[l], g.n_experts, g.hidden, rs.rows, fk::EPI_STORE_F32, c->at<float>(pl.off_moe_logits), g.n_experts, fk::Warm(), c->scratch()); }
   { Timed t(c, s, FOCUS_KC_ROUTE); fk::moe_route(s, a); fk::moe_group(s, a); }
   { Timed t(c, s, FOCUS_KC_EXPERTS); fk::moe_experts(s, a); }
   // the shared expert adds into the residual stream before the routed sum (both orders are the same sum)
@@ -694,7 +698,7 @@ int focus_step(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32_t *s
   // decode and verify
   void *normed = ctx->at<char>(pl.off_normed);
   { Timed t(ctx, s, FOCUS_KC_POINTWISE); fk::rmsnorm(s, g.dtype, resid_p, ctx->final_norm, normed, g.hidden, g.rms_eps, packed.rows); }
-  { Timed t(ctx, s, FOCUS_KC_GEMM); fk::gemm(s, g.dtype, normed, ctx->lm_head, g.vocab, g.hidden, packed.rows, fk::EPI_STORE_F32, logits, g.vocab); }
+  { Timed t(ctx, s, FOCUS_KC_GEMM); fk::gemm(s, g.dtype, normed, ctx->lm_head, g.vocab, g.hidden, packed.rows, fk::EPI_STORE_F32, logits, g.vocab, fk::Warm(), ctx->scratch()); }
   {
     Timed t(ctx, s, FOCUS_KC_DECODE);
     fk::confidence(s, logits, g.vocab, packed.rows, conf, amax);

@@ -61,7 +61,8 @@ enum Epilogue {
   EPI_STORE = 0,     // out[dtype] = acc
   EPI_ADD_F32 = 1,   // out[f32] += acc
   EPI_STORE_F32 = 2, // out[f32] = acc
-  EPI_SILU_MUL = 3   // W = [gate rows; up rows] (N = 2F): out[dtype][m, f] = silu(gate) * up; only where gemm_fuses_silu_mul()
+  EPI_SILU_MUL = 3,  // W = [gate rows; up rows] (N = 2F): out[dtype][m, f] = silu(gate) * up; only where gemm_fuses_silu_mul()
+  EPI_PARTIAL_SILU = 4   // internal to the K-split path: fp32 sums of the gate and up columns, weight-row order
 };
 bool gemm_fuses_silu_mul(int dtype, const void *A, const void *W, int N, int K);
 
@@ -74,8 +75,13 @@ struct Warm {
   const void *ptr = nullptr;
   size_t bytes = 0;
 };
+// Device memory a projection may use for the fp32 partial sums of a K-split launch (none: no such launches).
+struct Scratch {
+  void *ptr = nullptr;
+  size_t bytes = 0;
+};
 void gemm(hipStream_t s, int dtype, const void *A, const void *W, int N, int K, Rows rows, int epilogue,
-          void *out, int ldo, Warm warm = Warm());
+          void *out, int ldo, Warm warm = Warm(), Scratch scratch = Scratch());
 // Warm-up helper for kernels with one- or two-dimensional grids of short workgroups: the workgroups of the last round
 // (the last min(grid, 256) in launch order) each read one dword of every 128-byte line of their share.  Returns a value
 // the caller must keep alive (e.g. store it under a condition that never holds).

@@ -501,6 +501,7 @@ __global__ __launch_bounds__(64) void k_importance_mfma(ImpArgs a) {
         if (j > 0) v = fmaxf(v, row[j - 1]);
         if (j + 1 < BJ) v = fmaxf(v, row[j + 1]);
       }
+      v = j < B ? v : -INFINITY;                                  // no position beyond the block takes part in the softmax
       pooled[j] = v;
       m = fmaxf(m, v);
     }

@@ -252,8 +252,11 @@ __device__ __forceinline__ void lds_barrier() {
 template <int BM, int NW, int EPI>
 __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void k_gemm_pipe(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W, int N, int K,
                                                       Rows rows, void *out, int ldo, int tiles_m, int tiles_n, const void *warm,
-                                                      unsigned warm_bytes) {
+                                                      unsigned warm_bytes, int splits, size_t split_stride) {
 #if defined(__HIP_DEVICE_COMPILE__)   // buffer-resource builtins exist in the device pass only
+  // splits > 1: the K range is cut into `splits` parts, one workgroup each; part s writes its fp32 sums to
+  // out + s * split_stride and a second kernel adds the parts in order (EPI is then EPI_STORE_F32 or EPI_PARTIAL_SILU)
+  constexpr bool SILU_W = EPI == EPI_SILU_MUL || EPI == EPI_PARTIAL_SILU;
   // NW = 8: wavefronts 2 x 4, each BM/2 x 64;  NW = 4: wavefronts 2 x 2, each BM/2 x 128 (a third fewer LDS reads per MFMA,
   // accumulators in the 256 accumulation registers a lone wavefront per SIMD can have)
   constexpr int BN = 256, BK = 64, WCOLS = NW / 2, WM = BM / 2, WN = BN / WCOLS, TM = WM / 32, TN = WN / 32;
@@ -265,15 +268,19 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void k_gemm_pipe(const bf
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds_pipe[];
   unsigned char *const lds = lds_pipe;
   const int M = rows.count ? min(*rows.count, rows.cap) : rows.cap;
-  const int total = tiles_m * tiles_n;
+  const int total = tiles_m * tiles_n * splits;
   const int per_xcd = (total + 7) / 8;
-  const int tile = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
-  if (blockIdx.x / 8 >= per_xcd || tile >= total) return;
+  const int work = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  if (blockIdx.x / 8 >= per_xcd || work >= total) return;
+  const int tile = work / splits, split = work % splits;
   constexpr int GROUP = 8;
   const int in_group = tile % (GROUP * tiles_n), first_m = (tile / (GROUP * tiles_n)) * GROUP;
   const int gsz = min(tiles_m - first_m, GROUP);
-  const int m0 = (first_m + in_group % gsz) * BM, n0 = (in_group / gsz) * (EPI == EPI_SILU_MUL ? BN / 2 : BN);
+  const int m0 = (first_m + in_group % gsz) * BM, n0 = (in_group / gsz) * (SILU_W ? BN / 2 : BN);
   if (m0 >= M) return;
+  out = (void *)((float *)out + (size_t)split * split_stride);   // (split is 0 unless the output is fp32 partial sums)
+  const int nk = K / BK / splits;                                 // slabs of this workgroup; even (checked by the host)
+  const unsigned k_base = (unsigned)split * (unsigned)nk * (BK * 2);
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = (wave / WCOLS) * WM, wn = (wave % WCOLS) * WN;
   // raw buffers over the valid rows: an offset at or beyond the size reads zero without touching memory
@@ -284,15 +291,15 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void k_gemm_pipe(const bf
 #pragma unroll
   for (int q = 0; q < IA; ++q) {
     const int r = (wave * IA + q) * 8 + (lane >> 3), c = (lane & 7) ^ ((r >> 1) & 7);
-    voa[q] = (unsigned)(m0 + r) * (unsigned)K * 2u + c * 16;
+    voa[q] = (unsigned)(m0 + r) * (unsigned)K * 2u + k_base + c * 16;
   }
 #pragma unroll
   for (int q = 0; q < IB; ++q) {
     const int r = (wave * IB + q) * 8 + (lane >> 3), c = (lane & 7) ^ ((r >> 1) & 7);
     // fused SiLU*up: LDS rows 64 c .. 64 c + 31 hold the gate rows of output columns 32 c .. 32 c + 31, the next 32 rows the
     // matching up rows, so that a wavefront's column tiles 2 p and 2 p + 1 are gate and up of the same columns
-    const int wrow = EPI == EPI_SILU_MUL ? ((r >> 5) & 1) * (N / 2) + n0 + (r / 64) * 32 + (r & 31) : n0 + r;
-    vob[q] = (unsigned)wrow * (unsigned)K * 2u + c * 16;
+    const int wrow = SILU_W ? ((r >> 5) & 1) * (N / 2) + n0 + (r / 64) * 32 + (r & 31) : n0 + r;
+    vob[q] = (unsigned)wrow * (unsigned)K * 2u + k_base + c * 16;
   }
   // Optional: touch `warm_bytes` bytes at `warm` (the weights of the next projection) so that they wait in the memory-side
   // cache; weights are read once per step and a projection that finds them in HBM runs up to 1.5 times longer.  A
@@ -306,7 +313,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void k_gemm_pipe(const bf
   const int warm_groups = min((int)gridDim.x, 256), warm_rank = (int)blockIdx.x - ((int)gridDim.x - warm_groups);
   constexpr unsigned HIT = NW * 8192;   // bytes per hit: NW wavefronts x 64 lines
   const unsigned warm_hits = warm_rank < 0 ? 0u : ((warm_bytes + warm_groups - 1) / warm_groups + HIT - 1) / HIT;
-  const int warm_stride = warm_hits ? max(1, (K / BK) / (int)warm_hits) : 1;
+  const int warm_stride = warm_hits ? max(1, nk / (int)warm_hits) : 1;
   unsigned warm_off = (unsigned)max(warm_rank, 0) * (warm_hits * HIT), warm_left = warm_hits;
   int warm_next = 0;
   unsigned warm_sink = 0, warm_prev = 0;
@@ -340,7 +347,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void k_gemm_pipe(const bf
     if (f < TM) fa[slot][f < TM ? f : 0] = *(const bf16x8 *)(pa[ks] + buf * ASTAGE + (f < TM ? f : 0) * 4096);
     else fb[slot][f < TM ? 0 : f - TM] = *(const bf16x8 *)(pb[ks] + buf * WSTAGE + (f < TM ? 0 : f - TM) * 4096);
   };
-  const int nk = K / BK, last = (nk - 1) * (BK * 2);   // nk is even (checked by the host)
+  const int last = (nk - 1) * (BK * 2);
 #pragma unroll
   for (int i = 0; i < NI; ++i) gl(i, 0, 0);
 #pragma unroll
@@ -394,7 +401,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void k_gemm_pipe(const bf
   // A tile that lies inside the matrix takes the path without per-element bounds checks; there the accumulating
   // epilogue reads a whole row of 32x32 tiles before it adds and stores (one memory round trip per tile row instead
   // of one per element).
-  const bool inside = m0 + BM <= M && n0 + (EPI == EPI_SILU_MUL ? BN / 2 : BN) <= (EPI == EPI_SILU_MUL ? N / 2 : N);
+  const bool inside = m0 + BM <= M && n0 + (SILU_W ? BN / 2 : BN) <= (SILU_W ? N / 2 : N);
   const int erow = m0 + wm + 4 * (lane >> 5), ecol = lane & 31;
   if (EPI == EPI_SILU_MUL) {
 #pragma unroll
@@ -407,6 +414,23 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void k_gemm_pipe(const bf
           const int gm = erow + i * 32 + 8 * (r >> 2) + (r & 3);
           const float g = acc[i][2 * jp][r], u = acc[i][2 * jp + 1][r];
           if (inside || (gm < M && gn < N / 2)) ((bf16_t *)out)[(size_t)gm * ldo + gn] = (bf16_t)(g / (1.0f + __expf(-g)) * u);
+        }
+    }
+    return;
+  }
+  if (EPI == EPI_PARTIAL_SILU) {   // fp32 partial sums in weight-row order: gate of column c at c, up at N / 2 + c
+#pragma unroll
+    for (int jp = 0; jp < TN / 2; ++jp) {
+      const int gn = n0 + (wn / 64 + jp) * 32 + ecol;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int gm = erow + i * 32 + 8 * (r >> 2) + (r & 3);
+          if (inside || (gm < M && gn < N / 2)) {
+            ((float *)out)[(size_t)gm * ldo + gn] = acc[i][2 * jp][r];
+            ((float *)out)[(size_t)gm * ldo + N / 2 + gn] = acc[i][2 * jp + 1][r];
+          }
         }
     }
     return;
@@ -435,22 +459,73 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void k_gemm_pipe(const bf
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int gm = erow + i * 32 + 8 * (r >> 2) + (r & 3);
-        if (inside || (gm < M && gn < N)) store_out<bf16_t, EPI>(out, (size_t)gm * ldo + gn, acc[i][j][r]);
+        if (inside || (gm < M && gn < N)) store_out<bf16_t, EPI == EPI_PARTIAL_SILU ? EPI_STORE_F32 : EPI>(out, (size_t)gm * ldo + gn, acc[i][j][r]);
       }
     }
 #endif
 }
 
+// Adds the fp32 partial sums of a K-split projection in split order and applies the epilogue.
+template <int EPI>
+__global__ __launch_bounds__(256) void k_splitk_reduce(const float *__restrict__ part, int splits, size_t split_stride, Rows rows, int N,
+                                                       void *out, int ldo) {
+  const int M = rows.count ? min(*rows.count, rows.cap) : rows.cap;
+  const int ncol = EPI == EPI_SILU_MUL ? N / 2 : N, per_row = ncol / 4;
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const int m = (int)(idx / per_row), c = (int)(idx % per_row) * 4;
+  if (m >= M) return;
+  float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b = a;
+  for (int s = 0; s < splits; ++s) {
+    const float *p = part + s * split_stride + (size_t)m * N + c;
+    const float4 v = *(const float4 *)p;
+    a.x += v.x; a.y += v.y; a.z += v.z; a.w += v.w;
+    if (EPI == EPI_SILU_MUL) {
+      const float4 u = *(const float4 *)(p + N / 2);
+      b.x += u.x; b.y += u.y; b.z += u.z; b.w += u.w;
+    }
+  }
+  const float r[4] = {a.x, a.y, a.z, a.w}, u[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const size_t o = (size_t)m * ldo + c + i;
+    if (EPI == EPI_SILU_MUL) ((bf16_t *)out)[o] = (bf16_t)(r[i] / (1.0f + __expf(-r[i])) * u[i]);
+    else store_out<bf16_t, EPI>(out, o, r[i]);
+  }
+}
+
 template <int BM, int NW, int EPI>
-static bool launch_pipe_epi(hipStream_t s, const bf16_t *a, const bf16_t *w, int N, int K, Rows rows, void *out, int ldo, int tiles_m, int tiles_n, Warm warm) {
+static bool launch_pipe_epi(hipStream_t s, const bf16_t *a, const bf16_t *w, int N, int K, Rows rows, void *out, int ldo, int tiles_m, int tiles_n, Warm warm,
+                            int splits = 1, size_t split_stride = 0) {
   constexpr int kLds = 2 * (BM + 256) * 128;
   static bool ready = false;             // the dynamic LDS size has to be allowed once per kernel
   if (!ready) {
     if (hipFuncSetAttribute((const void *)k_gemm_pipe<BM, NW, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, kLds) != hipSuccess) return false;
     ready = true;
   }
-  const int grid = ((tiles_m * tiles_n + 7) / 8) * 8;
-  k_gemm_pipe<BM, NW, EPI><<<grid, NW * 64, kLds, s>>>(a, w, N, K, rows, out, ldo, tiles_m, tiles_n, warm.ptr, (unsigned)std::min<size_t>(warm.bytes, 0x7fffffffu));
+  const int grid = ((tiles_m * tiles_n * splits + 7) / 8) * 8;
+  k_gemm_pipe<BM, NW, EPI><<<grid, NW * 64, kLds, s>>>(a, w, N, K, rows, out, ldo, tiles_m, tiles_n, warm.ptr, (unsigned)std::min<size_t>(warm.bytes, 0x7fffffffu),
+                                                      splits, split_stride);
+  return true;
+}
+
+// K-split launch for problems with too few tiles to occupy the chip (few rows: the projection is bound by streaming W,
+// and a CU cannot pull more than a fraction of a percent of the HBM bandwidth on its own): `splits` workgroups per tile
+// write fp32 partial sums to the scratch buffer, k_splitk_reduce adds them in a fixed order.
+static bool launch_split(hipStream_t s, const void *A, const void *W, int N, int K, Rows rows, int epi, void *out, int ldo, Warm warm,
+                         int splits, float *scratch) {
+  const int tiles_m = (rows.cap + 127) / 128;
+  const int tiles_n = epi == EPI_SILU_MUL ? (N / 2 + 127) / 128 : (N + 255) / 256;
+  const bf16_t *a = (const bf16_t *)A, *w = (const bf16_t *)W;
+  const size_t stride = (size_t)rows.cap * N;
+  const bool ok = epi == EPI_SILU_MUL ? launch_pipe_epi<128, 8, EPI_PARTIAL_SILU>(s, a, w, N, K, rows, scratch, N, tiles_m, tiles_n, warm, splits, stride)
+                                      : launch_pipe_epi<128, 8, EPI_STORE_F32>(s, a, w, N, K, rows, scratch, N, tiles_m, tiles_n, warm, splits, stride);
+  if (!ok) return false;
+  const size_t quads = (size_t)rows.cap * ((epi == EPI_SILU_MUL ? N / 2 : N) / 4);
+  const unsigned grid = (unsigned)((quads + 255) / 256);
+  if (epi == EPI_SILU_MUL) k_splitk_reduce<EPI_SILU_MUL><<<grid, 256, 0, s>>>(scratch, splits, stride, rows, N, out, ldo);
+  else if (epi == EPI_STORE) k_splitk_reduce<EPI_STORE><<<grid, 256, 0, s>>>(scratch, splits, stride, rows, N, out, ldo);
+  else if (epi == EPI_ADD_F32) k_splitk_reduce<EPI_ADD_F32><<<grid, 256, 0, s>>>(scratch, splits, stride, rows, N, out, ldo);
+  else k_splitk_reduce<EPI_STORE_F32><<<grid, 256, 0, s>>>(scratch, splits, stride, rows, N, out, ldo);
   return true;
 }
 
@@ -470,7 +545,7 @@ bool gemm_fuses_silu_mul(int dtype, const void *A, const void *W, int N, int K) 
 }
 
 void gemm(hipStream_t s, int dtype, const void *A, const void *W, int N, int K, Rows rows, int epilogue,
-          void *out, int ldo, Warm warm) {
+          void *out, int ldo, Warm warm, Scratch scratch) {
   if (rows.cap <= 0) return;
   if (dtype == FOCUS_F32) { launch_valu<float>(s, A, W, N, K, rows, epilogue, out, ldo); return; }
   const bool aligned = K % 64 == 0 && ((uintptr_t)A & 15) == 0 && ((uintptr_t)W & 15) == 0;
@@ -486,6 +561,16 @@ void gemm(hipStream_t s, int dtype, const void *A, const void *W, int N, int K, 
   const bool four = t256 >= 512;
   if (fits32 && choice == 256 && (four ? launch_pipe<256, 4>(s, A, W, N, K, rows, epilogue, out, ldo, warm) : launch_pipe<256, 8>(s, A, W, N, K, rows, epilogue, out, ldo, warm))) return;
   if (fits32 && choice == 128 && launch_pipe<128, 8>(s, A, W, N, K, rows, epilogue, out, ldo, warm)) return;
+  if (fits32 && choice == 0 && scratch.ptr && N % 8 == 0) {
+    // too few tiles for the chip: cut K so that about one workgroup per CU exists (each part an even number of slabs, at least 4)
+    const int nk = K / 64;
+    int splits = 1;
+    while (splits < 16 && t128 * (splits * 2) <= 256 && nk % (splits * 4) == 0 && nk / (splits * 2) >= 4 &&
+           (size_t)(splits * 2) * rows.cap * N * 4 <= scratch.bytes)
+      splits *= 2;
+    if (splits > 1 && launch_split(s, A, W, N, K, rows, epilogue, out, ldo, warm, splits, (float *)scratch.ptr)) return;
+    if (launch_pipe<128, 8>(s, A, W, N, K, rows, epilogue, out, ldo, warm)) return;
+  }
   const long tiles_big = (long)((rows.cap + 255) / 256) * ((N + 127) / 128);
   if (tiles_big >= 512) launch_mfma<256, 128>(s, A, W, N, K, rows, epilogue, out, ldo);
   else launch_mfma<128, 128>(s, A, W, N, K, rows, epilogue, out, ldo);

@@ -162,3 +162,17 @@ def test_c6_moe_mini_full_size_batch_and_expert_shapes():
     the GPU; the oracle is teacher-forced with the picks of the sampled sequence after checking them against its logits."""
     wl = fi.workload("c6_moe_mini", n_layers=4)
     run_full_and_compare(wl, [int(np.argmin(wl.prefix_lens()))])
+
+
+def test_c2_sdar4_small_batch_block4_topk2():
+    """BASELINE configs[1] as given (4 layers of the 8B shape, batch 32, prefix 512, block 4, top-k 2, one step): 128 rows
+    in the full-block phase and 64 after eviction, the regime where the projections are K-split."""
+    wl = fi.workload("c2_sdar4")
+    run_full_and_compare(wl, [0, 13, 31])
+
+
+def test_c3_llada36_batch128_one_step():
+    """BASELINE configs[2] at its full batch, lengths and depth (36 layers, batch 128, prefix U[256,2048], block 32, keep
+    ratio 0.25); one denoising step, one sampled sequence recomputed by the oracle."""
+    wl = fi.workload("c3_llada36")
+    run_full_and_compare(wl, [int(np.argmax(wl.prefix_lens()))])

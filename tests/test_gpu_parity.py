@@ -344,6 +344,12 @@ def test_small_bf16_moe_router_picks_are_valid_for_the_oracle_logits():
     sess.focus.focus_free()
 
 
+@pytest.mark.parametrize("B", [4, 24, 40])
+def test_small_bf16_block_sizes_below_the_key_tile(B):
+    """Block sizes that do not fill the 32-key tiles of the matrix-core importance kernel (pooling at the block's edge)."""
+    compare_steps(small_bf16(block_size=B, batch=6, keep_ratio=0.5, steps=2), 2, 2e-2, exact=False)
+
+
 def test_small_bf16_block64_override_empty_and_full():
     wl = small_bf16(block_size=64, budget_mode=3, batch=4, steps=2)
     compare_steps(wl, 2, 2e-2, exact=False, k_override=[0, 64, 17, 1])
