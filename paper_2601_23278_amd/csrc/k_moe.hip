@@ -120,22 +120,29 @@ __global__ __launch_bounds__(256) void k_moe_list(MoeArgs a) {
 // Expert-sorted rows: offs = exclusive prefix sum of the counts; entry list[e][j] becomes row offs[e] + j.  Also the list
 // of (expert, first row) tiles of kMoeTileRows rows that the grouped projections walk.
 __global__ __launch_bounds__(256) void k_moe_place(MoeArgs a) {
-  __shared__ int s_off, s_tile, s_cnt;
+  __shared__ int s_sum[4];     // rows before this expert, tiles before it, all rows, all tiles (integer adds: order-free)
   const int e = blockIdx.x, tid = threadIdx.x, E = a.n_experts;
-  if (tid == 0) {
-    int off = 0, tile = 0, my_off = 0, my_tile = 0;
-    for (int i = 0; i < E; ++i) {
-      if (i == e) { my_off = off; my_tile = tile; }
-      const int c = a.count[i];
-      off += c;
-      tile += (c + kMoeTileRows - 1) / kMoeTileRows;
-    }
-    s_off = my_off; s_tile = my_tile; s_cnt = a.count[e];
-    a.offs[e] = my_off;
-    if (e == 0) { a.offs[E] = off; *a.n_tiles = min(tile, a.n_tile_slots); }
+  if (tid < 4) s_sum[tid] = 0;
+  __syncthreads();
+  int rows_lt = 0, tiles_lt = 0, rows_all = 0, tiles_all = 0;
+  for (int i = tid; i < E; i += 256) {
+    const int c = a.count[i], t = (c + kMoeTileRows - 1) / kMoeTileRows;
+    rows_all += c; tiles_all += t;
+    if (i < e) { rows_lt += c; tiles_lt += t; }
+  }
+  for (int o = 32; o > 0; o >>= 1) {
+    rows_lt += __shfl_xor(rows_lt, o); tiles_lt += __shfl_xor(tiles_lt, o);
+    rows_all += __shfl_xor(rows_all, o); tiles_all += __shfl_xor(tiles_all, o);
+  }
+  if ((tid & 63) == 0) {
+    atomicAdd(&s_sum[0], rows_lt); atomicAdd(&s_sum[1], tiles_lt); atomicAdd(&s_sum[2], rows_all); atomicAdd(&s_sum[3], tiles_all);
   }
   __syncthreads();
-  const int off = s_off, cnt = s_cnt, k = a.k;
+  const int off = s_sum[0], first_tile = s_sum[1], cnt = a.count[e], k = a.k;
+  if (tid == 0) {
+    a.offs[e] = off;
+    if (e == 0) { a.offs[E] = s_sum[2]; *a.n_tiles = min(s_sum[3], a.n_tile_slots); }
+  }
   const int32_t *list = a.list + (size_t)e * a.rows.cap;
   for (int j = tid; j < cnt; j += 256) {
     const int ent = list[j];
@@ -144,7 +151,7 @@ __global__ __launch_bounds__(256) void k_moe_place(MoeArgs a) {
     a.aexp[off + j] = e;
   }
   for (int m = tid; m * kMoeTileRows < cnt; m += 256)
-    if (s_tile + m < a.n_tile_slots) { a.tile_e[s_tile + m] = e; a.tile_m0[s_tile + m] = m * kMoeTileRows; }
+    if (first_tile + m < a.n_tile_slots) { a.tile_e[first_tile + m] = e; a.tile_m0[first_tile + m] = m * kMoeTileRows; }
 }
 
 void moe_group(hipStream_t s, const MoeArgs &a) {
