@@ -116,8 +116,8 @@ def main():
                     help="also launch one 1 GiB device-to-device copy (a dispatch of known size for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on one GPU only (sequences are independent; see DESIGN.md for how the "
-              "path would shard); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (sequences are independent, so the path shards by "
+              "sequence with replicated weights); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import torch
