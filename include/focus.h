@@ -213,6 +213,16 @@ int focus_run_layers(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int3
  * Enqueues only (no host synchronisation). */
 int focus_finalize_blocks(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32_t *seq_slot, int32_t *finalized);
 
+/* Several steps per host call with the state updated on the device after every step (the "in-loop state update" that
+ * App. E.3.4 proposes so that a multi-loop engine can run the method): n_steps times focus_step and, when finalize != 0,
+ * focus_finalize_blocks, enqueued back to back.  Every step sees the statistics, the masked / processed / frozen sets and
+ * the prefix lengths that the step before it left, exactly as n_steps separate calls would; nothing returns to the host.
+ * Not for FOCUS_BUDGET_OVERRIDE (its budgets are per step).
+ *   decoded       device [n_seq] int64, += tokens each sequence decoded in these steps; or NULL
+ *   out           outputs of the LAST step, or NULL */
+int focus_run_steps(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32_t *seq_slot, int32_t n_steps, int32_t finalize,
+                    int64_t *decoded, const focus_step_out *out);
+
 /* Teacher forcing for mixture-of-experts layers: from now on focus_step and focus_run_layers use, for the row of block
  * position p of batch entry b in layer l, the experts experts[(l * max_batch * B + b * B + p) * k + j], j < k (distinct,
  * in 0..E-1; out-of-range values are clamped), with weights computed from the router logits as for the router's own pick.

@@ -80,6 +80,7 @@ def load_library() -> C.CDLL:
         "focus_run_layers": [P, P, I, P, P, P, I, I, P],
         "focus_finalize_blocks": [P, P, I, P, P],
         "focus_set_route_override": [P, P],
+        "focus_run_steps": [P, P, I, P, I, I, P, C.POINTER(focus_step_out)],
         "focus_get_state": [P, I, C.POINTER(focus_seq_state)],
         "focus_set_state": [P, I, C.POINTER(focus_seq_state)],
         "focus_set_timing": [P, I],
@@ -95,7 +96,7 @@ def load_library() -> C.CDLL:
 
 _lib = load_library()
 EXPORTS = ["focus_workspace_bytes", "focus_kv_pool_bytes", "focus_init", "focus_prefill_kv", "focus_step",
-           "focus_select_compact", "focus_commit", "focus_run_layers", "focus_finalize_blocks", "focus_set_route_override", "focus_get_state", "focus_set_state", "focus_set_timing",
+           "focus_select_compact", "focus_commit", "focus_run_layers", "focus_finalize_blocks", "focus_set_route_override", "focus_run_steps", "focus_get_state", "focus_set_state", "focus_set_timing",
            "focus_get_kernel_time", "focus_free", "focus_last_error"]
 
 
@@ -195,6 +196,11 @@ class Focus:
     def focus_finalize_blocks(self, n_seq: int, finalized: Optional[torch.Tensor] = None, seq_slot: Optional[torch.Tensor] = None,
                               stream=None):
         _check(_lib.focus_finalize_blocks(self._ctx, self._stream(stream), n_seq, _ptr(seq_slot), _ptr(finalized)), self._ctx)
+
+    def focus_run_steps(self, n_seq: int, n_steps: int, finalize: bool = True, decoded: Optional[torch.Tensor] = None,
+                        out: Optional[focus_step_out] = None, seq_slot: Optional[torch.Tensor] = None, stream=None):
+        _check(_lib.focus_run_steps(self._ctx, self._stream(stream), n_seq, _ptr(seq_slot), n_steps, int(finalize), _ptr(decoded),
+                                    None if out is None else C.byref(out)), self._ctx)
 
     def focus_set_route_override(self, experts: Optional[torch.Tensor]):
         self._route_override = experts       # borrowed by the library

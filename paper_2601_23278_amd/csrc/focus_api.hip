@@ -26,6 +26,7 @@ struct Plan {
   // mixture-of-experts work buffers (zero-sized for a dense model)
   size_t off_moe_logits, off_moe_idx, off_moe_w, off_moe_list, off_moe_count, off_moe_offs, off_moe_tile_e, off_moe_tile_m0,
       off_moe_ntiles, off_moe_pos, off_moe_arow, off_moe_aexp, off_moe_act, off_moe_y;
+  size_t off_n_dec;                  // tokens decoded by the current step of focus_run_steps
   size_t off_splitk, splitk_bytes;   // fp32 partial sums of K-split projections (launches with few rows)
   size_t bytes, part_entries;
   int table_stride, max_rows, max_pos, moe_tile_slots;
@@ -88,6 +89,7 @@ Plan make_plan(const focus_config &c) {
   p.off_order = take(nb * 4);
   p.off_uncached = take(nb * 8);
   p.off_finalized = take(nb * 4);
+  p.off_n_dec = take(nb * 4);
   p.splitk_bytes = c.dtype == FOCUS_BF16 ? (size_t)64 << 20 : 0;
   p.off_splitk = take(p.splitk_bytes);
   if (c.n_experts > 0) {
@@ -785,6 +787,27 @@ int focus_finalize_blocks(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const
     layer_rest(ctx, s, l, rs, resid, ctx->at<char>(pl.off_qkv), qkv_w, nullptr);   // a finished block sees all of itself
   }
   fk::finalize_advance(s, n_seq, B, seq_slot, st, done, g.mask_token_id);
+  HIP_TRY(ctx, hipGetLastError());
+  return FOCUS_OK;
+}
+
+int focus_run_steps(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32_t *seq_slot, int32_t n_steps, int32_t finalize,
+                    int64_t *decoded, const focus_step_out *out) {
+  if (int rc = check_batch(ctx, n_seq)) return rc;
+  if (n_steps < 0) return fail(ctx, FOCUS_EINVAL, "n_steps %d is negative", n_steps);
+  if (ctx->cfg.budget_mode == FOCUS_BUDGET_OVERRIDE) return fail(ctx, FOCUS_EINVAL, "budget_mode OVERRIDE takes its budgets per step: use focus_step");
+  if (n_seq == 0) return FOCUS_OK;
+  hipStream_t s = (hipStream_t)hip_stream;
+  focus_step_out inner{};
+  inner.n_decoded = ctx->at<int32_t>(ctx->plan.off_n_dec);
+  for (int i = 0; i < n_steps; ++i) {
+    focus_step_out o = (i == n_steps - 1 && out) ? *out : inner;
+    if (!o.n_decoded) o.n_decoded = inner.n_decoded;
+    if (int rc = focus_step(ctx, hip_stream, n_seq, seq_slot, nullptr, nullptr, &o)) return rc;
+    if (decoded) fk::add_counts(s, n_seq, o.n_decoded, decoded);
+    if (finalize)
+      if (int rc = focus_finalize_blocks(ctx, hip_stream, n_seq, seq_slot, nullptr)) return rc;
+  }
   HIP_TRY(ctx, hipGetLastError());
   return FOCUS_OK;
 }

@@ -219,6 +219,7 @@ void finalize_pick(hipStream_t s, int n_seq, int B, int page_size, const int32_t
                    int32_t *finalized);
 void finalize_advance(hipStream_t s, int n_seq, int B, const int32_t *seq_slot, SlotState st, const int32_t *finalized, int mask_id);
 void fill_u64(hipStream_t s, uint64_t *p, int n, uint64_t v);
+void add_counts(hipStream_t s, int n, const int32_t *counts, int64_t *totals);   // totals[i] += counts[i]
 void iota_rows(hipStream_t s, int32_t *row_map, int32_t *cu, int n_seq, int B, int32_t *total);
 // order[rank] = batch entry, ranked by descending prefix length (ties: lower entry first)
 void length_order(hipStream_t s, int n_seq, const int32_t *seq_slot, SlotState st, int32_t *order);

@@ -290,6 +290,15 @@ __global__ void k_fill_u64(uint64_t *p, int n, uint64_t v) {
   int i = blockIdx.x * 256 + threadIdx.x;
   if (i < n) p[i] = v;
 }
+__global__ void k_add_counts(int n, const int32_t *counts, int64_t *totals) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) totals[i] += counts[i];
+}
+
+void add_counts(hipStream_t s, int n, const int32_t *counts, int64_t *totals) {
+  if (n > 0) k_add_counts<<<(n + 255) / 256, 256, 0, s>>>(n, counts, totals);
+}
+
 void fill_u64(hipStream_t s, uint64_t *p, int n, uint64_t v) {
   if (n > 0) k_fill_u64<<<(n + 255) / 256, 256, 0, s>>>(p, n, v);
 }

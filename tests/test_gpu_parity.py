@@ -555,3 +555,47 @@ def test_finalize_skips_incomplete_blocks_and_sequences_without_room():
     assert fin.cpu().tolist() == [0] * n                         # complete, but no pages / positions planned for another block
     assert [sess.focus.focus_get_state(b).prefix_len for b in range(n)] == before
     sess.focus.focus_free()
+
+
+@pytest.mark.parametrize("budget_mode,intra_block_cache", [(1, 0), (2, 1)])
+def test_run_steps_equals_separate_steps_with_finalisation(budget_mode, intra_block_cache):
+    """Several steps per host call with the state updated on the device (App. E.3.4): bit-identical to the same steps
+    enqueued one call at a time, across a block boundary, with the dynamic budget reading the fresh statistics."""
+    pk, runner = _pk()
+    wl = fi.workload("c1_tiny", budget_mode=budget_mode, keep_ratio=0.5, conf_threshold=0.0013, extra_blocks=2,
+                     intra_block_cache=intra_block_cache, constraints=3 if budget_mode == 2 else 0)
+    n, B, steps = wl.batch, wl.block_size, 5
+
+    def snapshot(sess, outs):
+        torch.cuda.synchronize()
+        st = [sess.focus.focus_get_state(b) for b in range(n)]
+        return ([(s.prefix_len, s.total_steps, s.token_sum, s.mask_bits, s.processed_bits, s.cached_bits, list(s.tokens)[:B]) for s in st],
+                {k: v.cpu().numpy().copy() for k, v in outs.t.items()})
+
+    sess = runner.open_session(wl, DEV)
+    outs = Outs(pk, wl, n)
+    total = np.zeros(n, dtype=np.int64)
+    for i in range(steps):
+        sess.focus.focus_step(n, out=outs.struct)
+        total += outs.host()["n_decoded"]
+        sess.focus.focus_finalize_blocks(n)
+    want_state, want_out = snapshot(sess, outs)
+    kv_want = sess.kv_pool.cpu()
+    sess.focus.focus_free()
+
+    sess = runner.open_session(wl, DEV)
+    outs = Outs(pk, wl, n)
+    decoded = torch.zeros(n, dtype=torch.int64, device=DEV)
+    sess.focus.focus_run_steps(n, 2, finalize=True, decoded=decoded)
+    sess.focus.focus_run_steps(n, steps - 2, finalize=True, decoded=decoded, out=outs.struct)
+    got_state, got_out = snapshot(sess, outs)
+    assert got_state == want_state
+    assert max(s[0] for s in got_state) > max(sess.prefix_lens)            # some block was finalised on the way
+    T = int(want_out["cu_seqlens"][-1])
+    assert T > 0
+    for k in want_out:          # (the separate calls wrote every step's outputs: beyond the last step's T' rows theirs are older)
+        rows = T if k in ("row_map", "conf", "argmax", "hidden_packed", "logits") else len(want_out[k])
+        assert np.array_equal(got_out[k][:rows], want_out[k][:rows]), k
+    assert decoded.cpu().numpy().tolist() == total.tolist()
+    assert torch.equal(sess.kv_pool.cpu(), kv_want)
+    sess.focus.focus_free()
