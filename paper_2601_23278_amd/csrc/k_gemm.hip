@@ -249,7 +249,7 @@ __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-template <int BM, int NW, int EPI>
+template <int BM, int NW, int EPI, int BN = 256>
 __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void k_gemm_pipe(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W, int N, int K,
                                                       Rows rows, void *out, int ldo, int tiles_m, int tiles_n, const void *warm,
                                                       unsigned warm_bytes, int splits, size_t split_stride) {
@@ -259,7 +259,9 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void k_gemm_pipe(const bf
   constexpr bool SILU_W = EPI == EPI_SILU_MUL || EPI == EPI_PARTIAL_SILU;
   // NW = 8: wavefronts 2 x 4, each BM/2 x 64;  NW = 4: wavefronts 2 x 2, each BM/2 x 128 (a third fewer LDS reads per MFMA,
   // accumulators in the 256 accumulation registers a lone wavefront per SIMD can have)
-  constexpr int BN = 256, BK = 64, WCOLS = NW / 2, WM = BM / 2, WN = BN / WCOLS, TM = WM / 32, TN = WN / 32;
+  // BN = 192 (4 wavefronts of 128 x 96) exists for launches whose 256-wide tiles would leave a quarter of the CUs idle
+  constexpr int BK = 64, WCOLS = NW / 2, WM = BM / 2, WN = BN / WCOLS, TM = WM / 32, TN = WN / 32;
+  static_assert(WN % 32 == 0 && (BN / 8) % NW == 0 && (!SILU_W || TN % 2 == 0), "tile shape");
   constexpr int IA = BM / 8 / NW, IB = BN / 8 / NW, NI = IA + IB;
   constexpr int ASTAGE = BM * 128, WSTAGE = BN * 128, WBASE = 2 * ASTAGE, NMF = TM * TN;
   // loads issued in the k-step right behind the barrier; the rest follow in the first k-step of the next slab
@@ -493,17 +495,17 @@ __global__ __launch_bounds__(256) void k_splitk_reduce(const float *__restrict__
   }
 }
 
-template <int BM, int NW, int EPI>
+template <int BM, int NW, int EPI, int BN = 256>
 static bool launch_pipe_epi(hipStream_t s, const bf16_t *a, const bf16_t *w, int N, int K, Rows rows, void *out, int ldo, int tiles_m, int tiles_n, Warm warm,
                             int splits = 1, size_t split_stride = 0) {
-  constexpr int kLds = 2 * (BM + 256) * 128;
+  constexpr int kLds = 2 * (BM + BN) * 128;
   static bool ready = false;             // the dynamic LDS size has to be allowed once per kernel
   if (!ready) {
-    if (hipFuncSetAttribute((const void *)k_gemm_pipe<BM, NW, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, kLds) != hipSuccess) return false;
+    if (hipFuncSetAttribute((const void *)k_gemm_pipe<BM, NW, EPI, BN>, hipFuncAttributeMaxDynamicSharedMemorySize, kLds) != hipSuccess) return false;
     ready = true;
   }
   const int grid = ((tiles_m * tiles_n * splits + 7) / 8) * 8;
-  k_gemm_pipe<BM, NW, EPI><<<grid, NW * 64, kLds, s>>>(a, w, N, K, rows, out, ldo, tiles_m, tiles_n, warm.ptr, (unsigned)std::min<size_t>(warm.bytes, 0x7fffffffu),
+  k_gemm_pipe<BM, NW, EPI, BN><<<grid, NW * 64, kLds, s>>>(a, w, N, K, rows, out, ldo, tiles_m, tiles_n, warm.ptr, (unsigned)std::min<size_t>(warm.bytes, 0x7fffffffu),
                                                       splits, split_stride);
   return true;
 }
@@ -559,6 +561,16 @@ void gemm(hipStream_t s, int dtype, const void *A, const void *W, int N, int K, 
   // four wavefronts of 128 x 128 read a third less from LDS per MFMA: measured 4-5 % faster where a CU works through
   // several tiles (gate/up, vocabulary projection, full-block layers), no gain on single-round launches
   const bool four = t256 >= 512;
+  // one round of 256-wide tiles that leaves CUs idle (the QKV projection of 2048 rows: 192 tiles): 192-wide tiles fill them
+  const long t192 = N % 192 == 0 ? (long)((rows.cap + 255) / 256) * (N / 192) : 0;
+  if (fits32 && choice == 256 && !four && t256 < 240 && t192 > t256 && t192 <= 256 && epilogue != EPI_SILU_MUL) {
+    const int tm = (rows.cap + 255) / 256, tn = N / 192;
+    const bf16_t *a = (const bf16_t *)A, *w = (const bf16_t *)W;
+    const bool ok = epilogue == EPI_STORE ? launch_pipe_epi<256, 4, EPI_STORE, 192>(s, a, w, N, K, rows, out, ldo, tm, tn, warm)
+                  : epilogue == EPI_ADD_F32 ? launch_pipe_epi<256, 4, EPI_ADD_F32, 192>(s, a, w, N, K, rows, out, ldo, tm, tn, warm)
+                                            : launch_pipe_epi<256, 4, EPI_STORE_F32, 192>(s, a, w, N, K, rows, out, ldo, tm, tn, warm);
+    if (ok) return;
+  }
   if (fits32 && choice == 256 && (four ? launch_pipe<256, 4>(s, A, W, N, K, rows, epilogue, out, ldo, warm) : launch_pipe<256, 8>(s, A, W, N, K, rows, epilogue, out, ldo, warm))) return;
   if (fits32 && choice == 128 && launch_pipe<128, 8>(s, A, W, N, K, rows, epilogue, out, ldo, warm)) return;
   if (fits32 && choice == 0 && scratch.ptr && N % 8 == 0) {

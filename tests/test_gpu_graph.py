@@ -39,11 +39,12 @@ def _snapshot(t):
     return {k: v.cpu().numpy().copy() for k, v in t.items()}
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+@pytest.mark.parametrize("dtype", ["bf16", "fp32", "bf16-moe"])
 def test_captured_step_replays_match_eager(dtype):
     import paper_2601_23278_amd as pk
     from paper_2601_23278_amd import runner
-    wl = _small_bf16() if dtype == "bf16" else fi.workload("c1_tiny")
+    wl = fi.workload("c1_tiny") if dtype == "fp32" else _small_bf16() if dtype == "bf16" else \
+        _small_bf16(n_experts=16, experts_per_token=4, expert_ffn=128, shared_ffn=128, route_scale=1.5, first_moe_layer=0)
     n, steps = wl.batch, 4
 
     sess = runner.open_session(wl, DEV)
