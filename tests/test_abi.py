@@ -74,6 +74,28 @@ def test_sizes_and_config_errors_without_gpu():
         assert e.value.code == binding.FOCUS_EINVAL, field
 
 
+def test_selection_and_expert_config_errors_without_gpu():
+    moe = dict(n_experts=8, experts_per_token=2, expert_ffn=64, shared_ffn=32, first_moe_layer=1, route_scale=1.0)
+
+    def cfg(**over):
+        c = good_cfg()
+        for k, v in {**moe, **over}.items():
+            setattr(c, k, v)
+        return c
+    dense = pk.focus_workspace_bytes(good_cfg())
+    assert pk.focus_workspace_bytes(cfg()) > dense                       # the expert work buffers are planned
+    assert pk.focus_workspace_bytes(cfg(n_experts=0, experts_per_token=99)) == dense   # dense model: the rest is ignored
+    for over in [dict(n_experts=513), dict(n_experts=-1), dict(experts_per_token=0), dict(experts_per_token=9),
+                 dict(n_experts=64, experts_per_token=33), dict(expert_ffn=60), dict(shared_ffn=-8), dict(first_moe_layer=3),
+                 dict(route_scale=0.0), dict(selection=3), dict(selection=-1), dict(intra_block_cache=2)]:
+        with pytest.raises(pk.FocusError) as e:
+            pk.focus_workspace_bytes(cfg(**over))
+        assert e.value.code == binding.FOCUS_EINVAL, over
+    lib = binding._lib
+    assert lib.focus_run_steps(None, None, 1, None, 1, 1, None, None) == binding.FOCUS_EINVAL
+    assert lib.focus_set_route_override(None, None) == binding.FOCUS_EINVAL
+
+
 def test_init_rejects_null_and_reports_text():
     lib = binding._lib
     ctx = C.c_void_p()

@@ -480,6 +480,10 @@ def test_step_argument_errors():
         sess.focus.focus_prefill_kv([10_000], [[0]])       # prefix longer than planned
     with pytest.raises(pk.FocusError):
         sess.focus.focus_prefill_kv([8], [[999]])          # page outside the pool
+    with pytest.raises(pk.FocusError):
+        sess.focus.focus_run_steps(wl.batch, 2)            # per-step budgets cannot be looped
+    with pytest.raises(pk.FocusError):
+        sess.focus.focus_set_route_override(torch.zeros(8, dtype=torch.int32, device=DEV))   # dense model
     sess.focus.focus_free()
 
 
