@@ -703,7 +703,7 @@ int focus_step(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32_t *s
   { Timed t(ctx, s, FOCUS_KC_GEMM); fk::gemm(s, g.dtype, normed, ctx->lm_head, g.vocab, g.hidden, packed.rows, fk::EPI_STORE_F32, logits, g.vocab, fk::Warm(), ctx->scratch()); }
   {
     Timed t(ctx, s, FOCUS_KC_DECODE);
-    fk::confidence(s, logits, g.vocab, packed.rows, conf, amax);
+    fk::confidence(s, logits, g.vocab, packed.rows, conf, amax, ctx->scratch());
     fk::CommitArgs ca{n_seq, B, seq_slot, st, keep, cu, conf, amax, g.conf_threshold, g.mask_token_id, g.intra_block_cache, o.tokens, o.mask_bits, o.n_decoded};
     fk::commit(s, ca);
   }

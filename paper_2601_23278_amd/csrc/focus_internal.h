@@ -190,7 +190,7 @@ void moe_route(hipStream_t s, const MoeArgs &a);      // picks and weights
 void moe_group(hipStream_t s, const MoeArgs &a);      // entries sorted by expert, tile list
 void moe_experts(hipStream_t s, const MoeArgs &a);    // the two grouped projections
 void moe_combine(hipStream_t s, const MoeArgs &a);    // weighted sum into the residual stream
-void confidence(hipStream_t s, const float *logits, int vocab, Rows rows, float *conf, int32_t *argmax);
+void confidence(hipStream_t s, const float *logits, int vocab, Rows rows, float *conf, int32_t *argmax, Scratch scratch = Scratch());
 struct CommitArgs {
   int n_seq, B;
   const int32_t *seq_slot;

@@ -222,8 +222,89 @@ __global__ __launch_bounds__(256) void k_confidence(const float *__restrict__ lo
   }
 }
 
-void confidence(hipStream_t s, const float *logits, int vocab, Rows rows, float *conf, int32_t *argmax) {
-  if (rows.cap > 0) k_confidence<<<rows.cap, 256, 0, s>>>(logits, vocab, rows, conf, argmax);
+// Few rows: one workgroup per row leaves most of the chip idle while it walks 150 000 logits, so a row is cut into
+// kConfParts column ranges.  A part records its own maximum (lowest index on ties), where it is, and the sum of
+// exp(x - its maximum); the merge takes the overall maximum and adds the rescaled sums in part order.
+constexpr int kConfParts = 16;
+__global__ __launch_bounds__(256) void k_confidence_part(const float *__restrict__ logits, int vocab, Rows rows, float *part) {
+  __shared__ float smax[4], ssum[4];
+  __shared__ int sidx[4];
+  const int r = blockIdx.x, p = blockIdx.y;
+  const int M = rows.count ? min(*rows.count, rows.cap) : rows.cap;
+  if (r >= M) return;
+  const int chunk = ((vocab + kConfParts - 1) / kConfParts + 3) & ~3;
+  const int c0 = min(p * chunk, vocab), c1 = min(c0 + chunk, vocab);
+  const float *x = logits + (size_t)r * vocab;
+  const bool vec = (((size_t)x) & 15) == 0;
+  float m = -INFINITY;
+  int mi = 0x7fffffff;
+  const int nv = vec ? (c1 - c0) / 4 : 0;
+  for (int i = threadIdx.x; i < nv; i += 256) {
+    const float4 v = ((const float4 *)(x + c0))[i];
+    const int at = c0 + 4 * i;
+    if (v.x > m) { m = v.x; mi = at; }
+    if (v.y > m) { m = v.y; mi = at + 1; }
+    if (v.z > m) { m = v.z; mi = at + 2; }
+    if (v.w > m) { m = v.w; mi = at + 3; }
+  }
+  for (int i = c0 + 4 * nv + threadIdx.x; i < c1; i += 256) {
+    const float v = x[i];
+    if (v > m) { m = v; mi = i; }
+  }
+  for (int o = 32; o > 0; o >>= 1) {
+    const float om = __shfl_xor(m, o);
+    const int oi = __shfl_xor(mi, o);
+    if (om > m || (om == m && oi < mi)) { m = om; mi = oi; }
+  }
+  const int w = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) { smax[w] = m; sidx[w] = mi; }
+  __syncthreads();
+  m = smax[0]; mi = sidx[0];
+  for (int i = 1; i < 4; ++i)
+    if (smax[i] > m || (smax[i] == m && sidx[i] < mi)) { m = smax[i]; mi = sidx[i]; }
+  float sum = 0.f;
+  for (int i = threadIdx.x; i < nv; i += 256) {
+    const float4 v = ((const float4 *)(x + c0))[i];
+    sum += __expf(v.x - m) + __expf(v.y - m) + __expf(v.z - m) + __expf(v.w - m);
+  }
+  for (int i = c0 + 4 * nv + threadIdx.x; i < c1; i += 256) sum += __expf(x[i] - m);
+  for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+  if ((threadIdx.x & 63) == 0) ssum[w] = sum;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float *o = part + ((size_t)r * kConfParts + p) * 3;
+    o[0] = m;
+    o[1] = __int_as_float(mi);
+    o[2] = c1 > c0 ? ssum[0] + ssum[1] + ssum[2] + ssum[3] : 0.f;
+  }
+}
+
+__global__ __launch_bounds__(256) void k_confidence_merge(const float *__restrict__ part, Rows rows, float *conf, int32_t *argmax) {
+  const int r = blockIdx.x * 256 + threadIdx.x;
+  const int M = rows.count ? min(*rows.count, rows.cap) : rows.cap;
+  if (r >= M) return;
+  const float *p = part + (size_t)r * kConfParts * 3;
+  float m = -INFINITY;
+  int mi = 0x7fffffff;
+  for (int i = 0; i < kConfParts; ++i) {
+    const float pm = p[3 * i];
+    const int pi = __float_as_int(p[3 * i + 1]);
+    if (pm > m || (pm == m && pi < mi)) { m = pm; mi = pi; }
+  }
+  float sum = 0.f;
+  for (int i = 0; i < kConfParts; ++i) sum += p[3 * i + 2] * __expf(p[3 * i] - m);   // an empty part has sum 0 and maximum -inf: adds 0
+  conf[r] = 1.0f / sum;
+  argmax[r] = mi;
+}
+
+void confidence(hipStream_t s, const float *logits, int vocab, Rows rows, float *conf, int32_t *argmax, Scratch scratch) {
+  if (rows.cap <= 0) return;
+  if (rows.cap <= 512 && vocab >= 16384 && scratch.ptr && scratch.bytes >= (size_t)rows.cap * kConfParts * 12) {
+    k_confidence_part<<<dim3(rows.cap, kConfParts), 256, 0, s>>>(logits, vocab, rows, (float *)scratch.ptr);
+    k_confidence_merge<<<(rows.cap + 255) / 256, 256, 0, s>>>((const float *)scratch.ptr, rows, conf, argmax);
+    return;
+  }
+  k_confidence<<<rows.cap, 256, 0, s>>>(logits, vocab, rows, conf, argmax);
 }
 
 // ---------------------------------------------------------------------------------------------

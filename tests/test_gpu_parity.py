@@ -350,6 +350,11 @@ def test_small_bf16_block_sizes_below_the_key_tile(B):
     compare_steps(small_bf16(block_size=B, batch=6, keep_ratio=0.5, steps=2), 2, 2e-2, exact=False)
 
 
+def test_small_bf16_large_vocabulary_few_rows():
+    """Few rows and a large vocabulary: the confidence of a row is computed in column ranges and merged."""
+    compare_steps(small_bf16(vocab=20008, mask_token_id=20007, batch=3, steps=2), 2, 2e-2, exact=False)
+
+
 def test_small_bf16_block64_override_empty_and_full():
     wl = small_bf16(block_size=64, budget_mode=3, batch=4, steps=2)
     compare_steps(wl, 2, 2e-2, exact=False, k_override=[0, 64, 17, 1])
