@@ -492,14 +492,15 @@ def test_step_argument_errors():
     sess.focus.focus_free()
 
 
-@pytest.mark.parametrize("intra_block_cache", [0, 1])
-def test_multi_block_generation_with_finalize_fp32(intra_block_cache):
+@pytest.mark.parametrize("intra_block_cache,moe", [(0, False), (1, False), (0, True)])
+def test_multi_block_generation_with_finalize_fp32(intra_block_cache, moe):
     """Two blocks generated back to back: steps until a block has no masked position, focus_finalize_blocks, next
     block.  Tokens, masks, counters and prefix lengths must equal the oracle's at every step; at the end the whole
     cache (prompt + both generated blocks, every layer) must equal the oracle's.  With the delayed intra-block cache
     (Sec. 4.3) frozen positions take no part in the last forward and keep the K/V they have."""
     pk, runner = _pk()
-    wl = fi.workload("c1_tiny", keep_ratio=0.5, extra_blocks=2, intra_block_cache=intra_block_cache)
+    wl = fi.workload("c1_tiny", keep_ratio=0.5, extra_blocks=2, intra_block_cache=intra_block_cache,
+                     **(dict(n_layers=3, first_moe_layer=1, **MOE_TINY) if moe else {}))      # (prefill and finalisation route on their own)
     cfg, W, pool, states, lens, tables, n_pages = oracle_batch(wl)
     sess = runner.open_session(wl, DEV)
     n, B = wl.batch, wl.block_size
