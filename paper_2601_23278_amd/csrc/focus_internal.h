@@ -186,6 +186,9 @@ struct MoeArgs {
   int32_t *out_experts;               // optional outputs [row ids, k]
   float *out_weights;
 };
+// fp32 partial sums part[split][row][N] of a dense projection of few rows, by the weight-streaming kernel of the expert
+// projections (false: shape not taken)
+bool gemm_stream_partial(hipStream_t s, const void *A, const void *W, int N, int K, Rows rows, bool silu, int splits, float *part);
 void moe_route(hipStream_t s, const MoeArgs &a);      // picks and weights
 void moe_group(hipStream_t s, const MoeArgs &a);      // entries sorted by expert, tile list
 void moe_experts(hipStream_t s, const MoeArgs &a);    // the two grouped projections

@@ -513,6 +513,16 @@ static bool launch_pipe_epi(hipStream_t s, const bf16_t *a, const bf16_t *w, int
 // K-split launch for problems with too few tiles to occupy the chip (few rows: the projection is bound by streaming W,
 // and a CU cannot pull more than a fraction of a percent of the HBM bandwidth on its own): `splits` workgroups per tile
 // write fp32 partial sums to the scratch buffer, k_splitk_reduce adds them in a fixed order.
+static void launch_reduce(hipStream_t s, int N, Rows rows, int epi, void *out, int ldo, int splits, const float *scratch) {
+  const size_t stride = (size_t)rows.cap * N;
+  const size_t quads = (size_t)rows.cap * ((epi == EPI_SILU_MUL ? N / 2 : N) / 4);
+  const unsigned grid = (unsigned)((quads + 255) / 256);
+  if (epi == EPI_SILU_MUL) k_splitk_reduce<EPI_SILU_MUL><<<grid, 256, 0, s>>>(scratch, splits, stride, rows, N, out, ldo);
+  else if (epi == EPI_STORE) k_splitk_reduce<EPI_STORE><<<grid, 256, 0, s>>>(scratch, splits, stride, rows, N, out, ldo);
+  else if (epi == EPI_ADD_F32) k_splitk_reduce<EPI_ADD_F32><<<grid, 256, 0, s>>>(scratch, splits, stride, rows, N, out, ldo);
+  else k_splitk_reduce<EPI_STORE_F32><<<grid, 256, 0, s>>>(scratch, splits, stride, rows, N, out, ldo);
+}
+
 static bool launch_split(hipStream_t s, const void *A, const void *W, int N, int K, Rows rows, int epi, void *out, int ldo, Warm warm,
                          int splits, float *scratch) {
   const int tiles_m = (rows.cap + 127) / 128;
@@ -522,12 +532,7 @@ static bool launch_split(hipStream_t s, const void *A, const void *W, int N, int
   const bool ok = epi == EPI_SILU_MUL ? launch_pipe_epi<128, 8, EPI_PARTIAL_SILU>(s, a, w, N, K, rows, scratch, N, tiles_m, tiles_n, warm, splits, stride)
                                       : launch_pipe_epi<128, 8, EPI_STORE_F32>(s, a, w, N, K, rows, scratch, N, tiles_m, tiles_n, warm, splits, stride);
   if (!ok) return false;
-  const size_t quads = (size_t)rows.cap * ((epi == EPI_SILU_MUL ? N / 2 : N) / 4);
-  const unsigned grid = (unsigned)((quads + 255) / 256);
-  if (epi == EPI_SILU_MUL) k_splitk_reduce<EPI_SILU_MUL><<<grid, 256, 0, s>>>(scratch, splits, stride, rows, N, out, ldo);
-  else if (epi == EPI_STORE) k_splitk_reduce<EPI_STORE><<<grid, 256, 0, s>>>(scratch, splits, stride, rows, N, out, ldo);
-  else if (epi == EPI_ADD_F32) k_splitk_reduce<EPI_ADD_F32><<<grid, 256, 0, s>>>(scratch, splits, stride, rows, N, out, ldo);
-  else k_splitk_reduce<EPI_STORE_F32><<<grid, 256, 0, s>>>(scratch, splits, stride, rows, N, out, ldo);
+  launch_reduce(s, N, rows, epi, out, ldo, splits, scratch);
   return true;
 }
 
@@ -573,6 +578,19 @@ void gemm(hipStream_t s, int dtype, const void *A, const void *W, int N, int K, 
   }
   if (fits32 && choice == 256 && (four ? launch_pipe<256, 4>(s, A, W, N, K, rows, epilogue, out, ldo, warm) : launch_pipe<256, 8>(s, A, W, N, K, rows, epilogue, out, ldo, warm))) return;
   if (fits32 && choice == 128 && launch_pipe<128, 8>(s, A, W, N, K, rows, epilogue, out, ldo, warm)) return;
+  if (fits32 && choice == 0 && scratch.ptr && N % 8 == 0 && rows.cap <= 128) {
+    // one tile of rows: pure weight streaming.  The expert-projection kernel (two workgroups per CU, two weight slabs in
+    // flight each) with K cut so that about two workgroups per CU exist
+    const int nk = K / 64, tn = epilogue == EPI_SILU_MUL ? (N / 2 + 63) / 64 : (N + 127) / 128;
+    int splits = 1;
+    while (splits < 16 && (long)tn * (splits * 2) <= 512 && nk % (splits * 2) == 0 && nk / (splits * 2) >= 4 &&
+           (size_t)(splits * 2) * rows.cap * N * 4 <= scratch.bytes)
+      splits *= 2;
+    if (gemm_stream_partial(s, A, W, N, K, rows, epilogue == EPI_SILU_MUL, splits, (float *)scratch.ptr)) {
+      launch_reduce(s, N, rows, epilogue, out, ldo, splits, (const float *)scratch.ptr);
+      return;
+    }
+  }
   if (fits32 && choice == 0 && scratch.ptr && N % 8 == 0) {
     // too few tiles for the chip: cut K so that about one workgroup per CU exists (each part an even number of slabs, at least 4)
     const int nk = K / 64;

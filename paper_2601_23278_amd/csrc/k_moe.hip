@@ -181,15 +181,21 @@ struct GroupGemm {
   int tiles_n;
   void *out;
   int ldo;
+  // dense modes (one weight matrix, rows in place, K cut into `splits` parts that write fp32 partial sums)
+  Rows rows;
+  int tiles_m, splits;
+  size_t split_stride;
 };
+enum { GG_DOWN = 0, GG_GATE_UP = 1, GG_DENSE_PARTIAL = 2, GG_DENSE_PARTIAL_SILU = 3 };
 
 #define FK_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 constexpr int vmcnt_imm(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }   // s_waitcnt vmcnt(n) only
 constexpr int kGroupLds = (2 * kMoeTileRows + 3 * 128) * 128;
 
-template <bool GATE_UP>
+template <int MODE>
 __global__ __launch_bounds__(256, 2) void k_group_gemm(GroupGemm g) {
 #if defined(__HIP_DEVICE_COMPILE__)   // buffer-resource builtins exist in the device pass only
+  constexpr bool GATE_UP = MODE == GG_GATE_UP || MODE == GG_DENSE_PARTIAL_SILU, DENSE = MODE >= GG_DENSE_PARTIAL;
   constexpr int BM = kMoeTileRows, BN = 128, ASTAGE = BM * 128, WSTAGE = BN * 128, WBASE = 2 * ASTAGE;
   constexpr int IA = BM / 8 / 4, IB = BN / 8 / 4;   // load instructions per wavefront and slab
   static_assert(BM == 128, "wavefront layout below is 2 x 2 of 64 x 64");
@@ -197,13 +203,23 @@ __global__ __launch_bounds__(256, 2) void k_group_gemm(GroupGemm g) {
   unsigned char *const lds = lds_group;
   // work item = weight tile nt of row tile t, nt fastest; XCD x (workgroups x, x + 8, ...) takes a contiguous range, so
   // the workgroups that read the same rows share an L2
-  const int n_tiles = *g.n_tiles, total = n_tiles * g.tiles_n, per_xcd = (total + 7) / 8;
+  const int splits = DENSE ? g.splits : 1;
+  const int n_tiles = DENSE ? g.tiles_m : *g.n_tiles, total = n_tiles * g.tiles_n * splits, per_xcd = (total + 7) / 8;
   const int item = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
   if ((int)(blockIdx.x / 8) >= per_xcd || item >= total) return;
-  const int t = item / g.tiles_n, nt = item % g.tiles_n;
-  const int e = g.tile_e[t], m0 = g.tile_m0[t];
-  const int row0 = g.offs[e] + m0, valid = min(BM, g.count[e] - m0);
+  const int split = item % splits, t = item / splits / g.tiles_n, nt = item / splits % g.tiles_n;
+  int e = 0, m0 = t * BM, row0 = m0, valid;
+  if (DENSE) {
+    valid = min(BM, (g.rows.count ? min(*g.rows.count, g.rows.cap) : g.rows.cap) - m0);
+    if (valid <= 0) return;
+  } else {
+    e = g.tile_e[t]; m0 = g.tile_m0[t];
+    row0 = g.offs[e] + m0; valid = min(BM, g.count[e] - m0);
+  }
   const int N = g.N, K = g.K, n0 = nt * (GATE_UP ? BN / 2 : BN);
+  const int nk = K / 64 / splits;                      // slabs of this workgroup
+  const unsigned k_base = (unsigned)split * (unsigned)nk * 128u;
+  float *const out_part = (float *)g.out + (size_t)split * g.split_stride;   // dense modes
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
   __amdgpu_buffer_rsrc_t rs_a = __builtin_amdgcn_make_buffer_rsrc((void *)g.A, 0, g.a_bytes, 0x00020000);
@@ -213,16 +229,15 @@ __global__ __launch_bounds__(256, 2) void k_group_gemm(GroupGemm g) {
   for (int q = 0; q < IA; ++q) {
     const int r = (wave * IA + q) * 8 + (lane >> 3), c = (lane & 7) ^ ((r >> 1) & 7);
     const int srow = r < valid ? (g.src ? g.src[row0 + r] : row0 + r) : -1;
-    voa[q] = srow < 0 ? 0x80000000u : (unsigned)srow * (unsigned)K * 2u + c * 16;
+    voa[q] = srow < 0 ? 0x80000000u : (unsigned)srow * (unsigned)K * 2u + k_base + c * 16;
   }
 #pragma unroll
   for (int q = 0; q < IB; ++q) {
     const int r = (wave * IB + q) * 8 + (lane >> 3), c = (lane & 7) ^ ((r >> 1) & 7);
     const int wrow = GATE_UP ? ((r >> 5) & 1) * (N / 2) + n0 + (r / 64) * 32 + (r & 31) : n0 + r;
     const bool ok = GATE_UP ? n0 + (r / 64) * 32 + (r & 31) < N / 2 : wrow < N;
-    vob[q] = ok ? (unsigned)wrow * (unsigned)K * 2u + c * 16 : 0x80000000u;
+    vob[q] = ok ? (unsigned)wrow * (unsigned)K * 2u + k_base + c * 16 : 0x80000000u;
   }
-  const int nk = K / 64;
   // slab kt of an operand into a stage; beyond the last slab the offset is out of range: nothing moves
   auto issue_a = [&](int kt, int stage) {
     const unsigned so = kt < nk ? (unsigned)kt * 128u : 0x80000000u;
@@ -273,7 +288,19 @@ __global__ __launch_bounds__(256, 2) void k_group_gemm(GroupGemm g) {
   __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
   // accumulator register r of lane l is C[8 * (r / 4) + 4 * (l / 32) + r % 4][l % 32] of its 32 x 32 tile
   const int erow = wm + 4 * (lane >> 5), ecol = lane & 31;
-  if (GATE_UP) {
+  if (MODE == GG_DENSE_PARTIAL_SILU) {   // fp32 partial sums in weight-row order: gate of column c at c, up at N / 2 + c
+    const int gn = n0 + (wn / 64) * 32 + ecol;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int gm = erow + i * 32 + 8 * (r >> 2) + (r & 3);
+        if (gm < valid && gn < N / 2) {
+          out_part[(size_t)(row0 + gm) * g.ldo + gn] = acc[i][0][r];
+          out_part[(size_t)(row0 + gm) * g.ldo + N / 2 + gn] = acc[i][1][r];
+        }
+      }
+  } else if (GATE_UP) {
     const int gn = n0 + (wn / 64) * 32 + ecol;
 #pragma unroll
     for (int i = 0; i < 2; ++i)
@@ -292,7 +319,7 @@ __global__ __launch_bounds__(256, 2) void k_group_gemm(GroupGemm g) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int gm = erow + i * 32 + 8 * (r >> 2) + (r & 3);
-          if (gm < valid && gn < N) ((float *)g.out)[(size_t)(row0 + gm) * g.ldo + gn] = acc[i][j][r];
+          if (gm < valid && gn < N) (DENSE ? out_part : (float *)g.out)[(size_t)(row0 + gm) * g.ldo + gn] = acc[i][j][r];
         }
       }
   }
@@ -320,16 +347,28 @@ __global__ __launch_bounds__(256) void k_group_gemm_valu(const T *A, const int32
   else ((float *)out)[(size_t)row * ldo + col] = d0;
 }
 
-template <bool GATE_UP>
+template <int MODE>
 static bool launch_group(hipStream_t s, const GroupGemm &g, int n_tile_slots) {
   constexpr int kLds = kGroupLds;
   static bool ready = false;             // the dynamic LDS size has to be allowed once per kernel
   if (!ready) {
-    if (hipFuncSetAttribute((const void *)k_group_gemm<GATE_UP>, hipFuncAttributeMaxDynamicSharedMemorySize, kLds) != hipSuccess) return false;
+    if (hipFuncSetAttribute((const void *)k_group_gemm<MODE>, hipFuncAttributeMaxDynamicSharedMemorySize, kLds) != hipSuccess) return false;
     ready = true;
   }
-  k_group_gemm<GATE_UP><<<((n_tile_slots * g.tiles_n + 7) / 8) * 8, 256, kLds, s>>>(g);
+  k_group_gemm<MODE><<<((n_tile_slots * g.tiles_n * (MODE >= GG_DENSE_PARTIAL ? g.splits : 1) + 7) / 8) * 8, 256, kLds, s>>>(g);
   return true;
+}
+
+// Dense projection of few rows (at most a few 128-row tiles) as fp32 partial sums of `splits` K ranges, part[split][row][N]
+// (SiLU variant: gate and up sums in weight-row order): the weight-streaming kernel above with one "expert".
+bool gemm_stream_partial(hipStream_t s, const void *A, const void *W, int N, int K, Rows rows, bool silu, int splits, float *part) {
+  if (K % (64 * splits) || (double)rows.cap * K * 2 >= 2.0e9 || (double)N * K * 2 >= 4.0e9 || ((uintptr_t)A & 15) || ((uintptr_t)W & 15)) return false;
+  GroupGemm g{};
+  g.A = (const bf16_t *)A; g.a_bytes = (unsigned)((size_t)rows.cap * K * 2); g.W = (const bf16_t *)W; g.N = N; g.K = K;
+  g.tiles_n = silu ? (N / 2 + 63) / 64 : (N + 127) / 128;
+  g.out = part; g.ldo = N; g.rows = rows; g.tiles_m = (rows.cap + kMoeTileRows - 1) / kMoeTileRows; g.splits = splits;
+  g.split_stride = (size_t)rows.cap * N;
+  return silu ? launch_group<GG_DENSE_PARTIAL_SILU>(s, g, g.tiles_m) : launch_group<GG_DENSE_PARTIAL>(s, g, g.tiles_m);
 }
 
 void moe_experts(hipStream_t s, const MoeArgs &a) {
@@ -343,7 +382,7 @@ void moe_experts(hipStream_t s, const MoeArgs &a) {
                 a.offs, a.count, a.tile_e, a.tile_m0, a.n_tiles, (Fe + 63) / 64, a.act, Fe};
     GroupGemm d{(const bf16_t *)a.act, (unsigned)((size_t)cap * Fe * 2), nullptr, (const bf16_t *)a.w_down, h, Fe,
                 a.offs, a.count, a.tile_e, a.tile_m0, a.n_tiles, (h + 127) / 128, a.y, h};
-    if (launch_group<true>(s, g, a.n_tile_slots) && launch_group<false>(s, d, a.n_tile_slots)) return;
+    if (launch_group<GG_GATE_UP>(s, g, a.n_tile_slots) && launch_group<GG_DOWN>(s, d, a.n_tile_slots)) return;
   }
   if (a.dtype == FOCUS_BF16) {
     k_group_gemm_valu<bf16_t, true><<<dim3(cap, (Fe + 255) / 256), 256, 0, s>>>((const bf16_t *)a.u, a.arow, (const bf16_t *)a.w_gate_up, 2 * Fe, h, a.offs, a.aexp, a.n_experts, a.act, Fe);
