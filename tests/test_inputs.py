@@ -58,3 +58,24 @@ def test_workload_recipes():
     assert sorted(flat) == list(range(n5)) and flat != sorted(flat)                 # a real permutation
     toks = fi.workload("c1_tiny").prompt_tokens()
     assert all(1 <= t < 1024 for row in toks for t in row)
+
+
+def test_expert_weights_and_forced_routes():
+    wl = fi.workload("c1_tiny", n_experts=8, experts_per_token=3, expert_ffn=16, shared_ffn=8, first_moe_layer=1, n_layers=3)
+    assert [wl.is_moe_layer(l) for l in range(3)] == [False, True, True]
+    shapes = wl.moe_weight_shapes()
+    assert shapes["w_expert_gate_up"] == (8, 32, wl.hidden) and shapes["w_expert_down"] == (8, wl.hidden, 16)
+    w1, w2 = wl.moe_weight(1, "w_expert_gate_up"), wl.moe_weight(2, "w_expert_gate_up")
+    assert torch.equal(w1, wl.moe_weight(1, "w_expert_gate_up")) and not torch.equal(w1, w2)       # pure function of (seed, layer, tensor)
+    assert abs(float(w1.std()) - fi.WEIGHT_STD) < 0.1 * fi.WEIGHT_STD
+    # an expert's slice is the same stream whichever way it is generated (flat index = row-major offset)
+    e = 5
+    per = 32 * wl.hidden
+    part = fi.normal_values(wl.seed, fi.TID_MOE0 + 8 * 1 + 1, e * per, per, fi.WEIGHT_STD).view(32, wl.hidden)
+    assert torch.equal(part, w1[e])
+    routes = wl.route_override(2)
+    assert len(routes) == 3 and len(routes[0]) == 2 * wl.block_size
+    assert all(len(set(r)) == 3 and all(0 <= x < 8 for x in r) for layer in routes for r in layer)
+    assert routes == wl.route_override(2) and routes[1] != routes[2]
+    counts = np.bincount([x for layer in routes for r in layer for x in r], minlength=8)
+    assert counts.min() > 0                                                                        # every expert gets rows
