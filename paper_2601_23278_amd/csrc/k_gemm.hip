@@ -586,7 +586,8 @@ void gemm(hipStream_t s, int dtype, const void *A, const void *W, int N, int K, 
     while (splits < 16 && (long)tn * (splits * 2) <= 512 && nk % (splits * 2) == 0 && nk / (splits * 2) >= 4 &&
            (size_t)(splits * 2) * rows.cap * N * 4 <= scratch.bytes)
       splits *= 2;
-    if (gemm_stream_partial(s, A, W, N, K, rows, epilogue == EPI_SILU_MUL, splits, (float *)scratch.ptr)) {
+    if ((size_t)splits * rows.cap * N * 4 <= scratch.bytes &&
+        gemm_stream_partial(s, A, W, N, K, rows, epilogue == EPI_SILU_MUL, splits, (float *)scratch.ptr)) {
       launch_reduce(s, N, rows, epilogue, out, ldo, splits, (const float *)scratch.ptr);
       return;
     }
