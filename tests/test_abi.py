@@ -104,3 +104,28 @@ def test_init_rejects_null_and_reports_text():
     assert rc == binding.FOCUS_EINVAL and b"null" in lib.focus_last_error(None)
     assert lib.focus_step(None, None, 1, None, None, None, None) == binding.FOCUS_EINVAL
     assert lib.focus_free(None) == binding.FOCUS_OK
+
+
+def test_binding_fails_loudly_without_the_library_and_never_touches_the_oracle(tmp_path):
+    """The product path has no fallback: with libfocus.so out of reach the import raises, and neither the binding nor
+    the runner imports anything from oracle/."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    pkg = os.path.join(root, "paper_2601_23278_amd")
+    # a copy of the package's Python files without the built library
+    dst = tmp_path / "paper_2601_23278_amd"
+    dst.mkdir()
+    for f in os.listdir(pkg):
+        if f.endswith(".py"):
+            (dst / f).write_text(open(os.path.join(pkg, f)).read())
+    code = "import sys; sys.path.insert(0, %r); sys.path.insert(1, %r)\ntry:\n    import paper_2601_23278_amd\nexcept ImportError as e:\n    print('IMPORT-ERROR', e)\n" % (str(tmp_path), root)
+    out = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=120).stdout
+    assert "IMPORT-ERROR" in out and "libfocus.so is not built" in out
+    for f in ("binding.py", "runner.py", "__init__.py", "build.py"):
+        src = open(os.path.join(pkg, f)).read()
+        assert "oracle" not in src, f
+    csrc = os.path.join(pkg, "csrc")
+    for f in os.listdir(csrc):
+        text = open(os.path.join(csrc, f)).read()
+        assert "oracle/" not in text and not [l for l in text.splitlines() if l.startswith("#include") and "oracle" in l], f
