@@ -112,6 +112,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seqs", type=int, default=96)
     ap.add_argument("--cpu-layers", type=int, default=6)
+    ap.add_argument("--constant-weights", action="store_true",
+                    help="diagnostic: overwrite every weight with one constant, so that the matrix cores see operands that do not "
+                         "toggle (shows how much of the projection time is the chip's power limit); the JSON says so")
     ap.add_argument("--pmc-calibrate", action="store_true",
                     help="also launch one 1 GiB device-to-device copy (a dispatch of known size for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -137,6 +140,10 @@ def main():
     ratio0 = wl.keep_ratio if wl.budget_mode == 1 else wl.topk / wl.block_size      # fraction of the block that is retained
     t_setup = time.time()
     sess = runner.open_session(wl, "cuda:0")
+    if args.constant_weights:
+        embed, lm_head, norm, layers = sess.weights
+        for t in [embed, lm_head] + [w for layer in layers for k, w in layer.items() if k.startswith("w_")]:
+            t.fill_(0.01)
     torch.cuda.synchronize()
     t_setup = time.time() - t_setup
     n, B = wl.batch, wl.block_size
@@ -240,7 +247,7 @@ def main():
     line = {
         "metric": "decoded tokens/s at batch %d (%s, bf16, 1 GPU)" % (n, "8B-shaped" if not wl.n_experts else "mixture-of-experts, 16B total / 1.4B active shape"), "value": round(head["decoded_tokens_per_s"], 2),
         "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(head["ms_per_step"], 3),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic" if not args.constant_weights else "synthetic, every weight overwritten with 0.01 (diagnostic run)",
         "config": {"workload": "%s: %d layers, hidden %d, %dq/%dkv x %d, ffn %d, vocab %d, batch %d, prefix %s[%d,%d], block %d, keep ratio %.3f"
                                % (wl.name, wl.n_layers, wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, wl.vocab, n,
                                   wl.prefix_dist, wl.prefix_lo, wl.prefix_hi, B, ratio0),
