@@ -563,9 +563,9 @@ void gemm(hipStream_t s, int dtype, const void *A, const void *W, int N, int K, 
   const bool fits32 = (double)std::max(rows.cap + 256, N + 256) * K * 2 < 4.0e9 && (K / 64) % 2 == 0;
   const long t256 = (long)((rows.cap + 255) / 256) * n_tiles, t128 = (long)((rows.cap + 127) / 128) * n_tiles;
   const int choice = t256 >= 160 ? 256 : (t128 >= 160 ? 128 : 0);
-  // four wavefronts of 128 x 128 read a third less from LDS per MFMA: measured 4-5 % faster where a CU works through
-  // several tiles (gate/up, vocabulary projection, full-block layers), no gain on single-round launches
-  const bool four = t256 >= 512;
+  // four wavefronts of 128 x 128 read a third less from LDS per MFMA: measured 2-5 % faster where the launch takes more
+  // than one round of workgroups (gate/up, vocabulary projection, full-block layers), no gain on single-round launches
+  const bool four = t256 > 256;
   // one round of 256-wide tiles that leaves CUs idle (the QKV projection of 2048 rows: 192 tiles): 192-wide tiles fill them
   const long t192 = N % 192 == 0 ? (long)((rows.cap + 255) / 256) * (N / 192) : 0;
   if (fits32 && choice == 256 && !four && t256 < 240 && t192 > t256 && t192 <= 256 && epilogue != EPI_SILU_MUL) {
