@@ -173,51 +173,51 @@ void scan_compact(hipStream_t s, int n_seq, int B, const uint64_t *keep_bits, in
 
 // ---------------------------------------------------------------------------------------------
 // Confidence of a row of logits: arg-max (lowest id on ties) and 1 / sum exp(logit - max).
+// One pass over the row: every lane keeps a running maximum (with its index: ascending index per lane, so the first
+// maximum is kept) and the sum of exp(x - maximum so far), rescaled when the maximum grows; lanes are merged as
+// (maximum, sum) pairs, lowest index on equal maxima.
+__device__ __forceinline__ void conf_push(float v, int i, float &m, int &mi, float &s) {
+  if (v > m) { s = s * __expf(m - v) + 1.0f; m = v; mi = i; }
+  else s += v == -INFINITY ? 0.f : __expf(v - m);     // (a row that starts with -inf: exp(-inf + inf) is not a number)
+}
+__device__ __forceinline__ void conf_merge(float om, int oi, float os, float &m, int &mi, float &s) {
+  const float big = fmaxf(m, om);
+  const float a = m == big ? 1.0f : __expf(m - big), b = om == big ? 1.0f : __expf(om - big);
+  s = s * a + os * b;
+  if (om > m || (om == m && oi < mi)) mi = oi;
+  m = big;
+}
 __global__ __launch_bounds__(256) void k_confidence(const float *__restrict__ logits, int vocab, Rows rows, float *conf,
                                                     int32_t *argmax) {
-  __shared__ float smax[4];
+  __shared__ float smax[4], ssum[4];
   __shared__ int sidx[4];
-  __shared__ float ssum[4];
   const int r = blockIdx.x;
   const int M = rows.count ? min(*rows.count, rows.cap) : rows.cap;
   if (r >= M) return;
   const float *x = logits + (size_t)r * vocab;
   const int nv = ((size_t)x & 15) == 0 ? vocab / 4 : 0;       // 16-byte pieces when the row is aligned
-  float m = -INFINITY;
+  float m = -INFINITY, sum = 0.f;
   int mi = 0x7fffffff;
   for (int i = threadIdx.x; i < nv; i += 256) {
     const float4 v = ((const float4 *)x)[i];
-    if (v.x > m) { m = v.x; mi = 4 * i; }          // ascending index per lane: the first maximum is kept
-    if (v.y > m) { m = v.y; mi = 4 * i + 1; }
-    if (v.z > m) { m = v.z; mi = 4 * i + 2; }
-    if (v.w > m) { m = v.w; mi = 4 * i + 3; }
+    conf_push(v.x, 4 * i, m, mi, sum);
+    conf_push(v.y, 4 * i + 1, m, mi, sum);
+    conf_push(v.z, 4 * i + 2, m, mi, sum);
+    conf_push(v.w, 4 * i + 3, m, mi, sum);
   }
-  for (int i = 4 * nv + threadIdx.x; i < vocab; i += 256) {
-    float v = x[i];
-    if (v > m) { m = v; mi = i; }
-  }
+  for (int i = 4 * nv + threadIdx.x; i < vocab; i += 256) conf_push(x[i], i, m, mi, sum);
   for (int o = 32; o > 0; o >>= 1) {
-    float om = __shfl_xor(m, o);
-    int oi = __shfl_xor(mi, o);
-    if (om > m || (om == m && oi < mi)) { m = om; mi = oi; }
+    const float om = __shfl_xor(m, o), os = __shfl_xor(sum, o);
+    const int oi = __shfl_xor(mi, o);
+    conf_merge(om, oi, os, m, mi, sum);
   }
   const int w = threadIdx.x >> 6;
-  if ((threadIdx.x & 63) == 0) { smax[w] = m; sidx[w] = mi; }
-  __syncthreads();
-  m = smax[0]; mi = sidx[0];
-  for (int i = 1; i < 4; ++i)
-    if (smax[i] > m || (smax[i] == m && sidx[i] < mi)) { m = smax[i]; mi = sidx[i]; }
-  float sum = 0.f;
-  for (int i = threadIdx.x; i < nv; i += 256) {
-    const float4 v = ((const float4 *)x)[i];
-    sum += __expf(v.x - m) + __expf(v.y - m) + __expf(v.z - m) + __expf(v.w - m);
-  }
-  for (int i = 4 * nv + threadIdx.x; i < vocab; i += 256) sum += __expf(x[i] - m);
-  for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
-  if ((threadIdx.x & 63) == 0) ssum[w] = sum;
+  if ((threadIdx.x & 63) == 0) { smax[w] = m; sidx[w] = mi; ssum[w] = sum; }
   __syncthreads();
   if (threadIdx.x == 0) {
-    conf[r] = 1.0f / (ssum[0] + ssum[1] + ssum[2] + ssum[3]);
+    m = smax[0]; mi = sidx[0]; sum = ssum[0];
+    for (int i = 1; i < 4; ++i) conf_merge(smax[i], sidx[i], ssum[i], m, mi, sum);
+    conf[r] = 1.0f / sum;
     argmax[r] = mi;
   }
 }
