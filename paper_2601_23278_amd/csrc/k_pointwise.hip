@@ -157,9 +157,8 @@ __global__ __launch_bounds__(256) void k_rope_kv_write(T *qkv, int Hq, Rows rows
 }
 
 // bf16: eight rotation pairs per thread step, 16-byte loads and stores (q, k in place; k also into its cache row).
-__global__ __launch_bounds__(256) void k_rope_kv_write_bf16(bf16_t *qkv, int Hq, Rows rows, RowIndex ri, SlotState st, KvLayer kv,
-                                                            const float2 *rope, int write_v) {
-  const int r = blockIdx.x;
+__device__ __forceinline__ void rope_kv_write_row(int r, bf16_t *qkv, int Hq, Rows rows, RowIndex ri, SlotState st, KvLayer kv,
+                                                  const float2 *rope, int write_v) {
   if (r >= n_rows(rows)) return;
   const int D = kv.head_dim, half = D / 2, Hkv = kv.n_kv_heads, P = kv.page_size, upr = half / 8;   // units per head
   const int rm = ri.row_map[r], b = rm / ri.B, p = rm % ri.B;
@@ -197,8 +196,7 @@ __global__ __launch_bounds__(256) void k_rope_kv_write_bf16(bf16_t *qkv, int Hq,
 // V cache write of all rows of one (sequence, kv head).  V is kept transposed, [H_kv][D][page_size], so the values of
 // one row are 128 bytes apart; eight neighbouring lanes take eight rows of the same d, which fall into the same
 // 128-byte line (one write transaction instead of eight).
-__global__ __launch_bounds__(256) void k_v_write_bf16(const bf16_t *qkv, int Hq, const int32_t *cu, RowIndex ri, SlotState st, KvLayer kv) {
-  const int b = blockIdx.x, hk = blockIdx.y;
+__device__ __forceinline__ void v_write_group(int b, int hk, const bf16_t *qkv, int Hq, const int32_t *cu, RowIndex ri, SlotState st, KvLayer kv) {
   const int r0 = cu[b], nr = cu[b + 1] - r0;
   if (nr <= 0) return;
   const int D = kv.head_dim, Hkv = kv.n_kv_heads, P = kv.page_size, stride = (Hq + 2 * Hkv) * D;
@@ -215,13 +213,22 @@ __global__ __launch_bounds__(256) void k_v_write_bf16(const bf16_t *qkv, int Hq,
   }
 }
 
+// One launch for both: the first n_seq * H_kv workgroups write V (they read columns the rotation does not touch), the rest
+// rotate one row each and write its K.
+__global__ __launch_bounds__(256) void k_rope_kv_write_bf16(bf16_t *qkv, int Hq, Rows rows, RowIndex ri, SlotState st, KvLayer kv,
+                                                            const float2 *rope, int n_seq, const int32_t *cu) {
+  const int v_groups = n_seq * kv.n_kv_heads;
+  if ((int)blockIdx.x < v_groups) v_write_group(blockIdx.x / kv.n_kv_heads, blockIdx.x % kv.n_kv_heads, qkv, Hq, cu, ri, st, kv);
+  else rope_kv_write_row(blockIdx.x - v_groups, qkv, Hq, rows, ri, st, kv, rope, n_seq > 0 ? 0 : 1);
+}
+
 void rope_kv_write(hipStream_t s, int dtype, void *qkv, int n_q_heads, Rows rows, RowIndex ri, SlotState st,
                    KvLayer kv, const float2 *rope_table, int n_seq, const int32_t *cu) {
   if (rows.cap <= 0) return;
   if (dtype == FOCUS_BF16 && kv.head_dim % 16 == 0 && (((uintptr_t)qkv | (uintptr_t)kv.base) & 15) == 0) {
     const bool by_seq = cu != nullptr && n_seq > 0;      // the V scatter per (sequence, kv head) when the row ranges are known
-    k_rope_kv_write_bf16<<<rows.cap, 256, 0, s>>>((bf16_t *)qkv, n_q_heads, rows, ri, st, kv, rope_table, by_seq ? 0 : 1);
-    if (by_seq) k_v_write_bf16<<<dim3(n_seq, kv.n_kv_heads), 256, 0, s>>>((const bf16_t *)qkv, n_q_heads, cu, ri, st, kv);
+    const int groups = by_seq ? n_seq * kv.n_kv_heads : 0;
+    k_rope_kv_write_bf16<<<groups + rows.cap, 256, 0, s>>>((bf16_t *)qkv, n_q_heads, rows, ri, st, kv, rope_table, by_seq ? n_seq : 0, cu);
     return;
   }
   if (dtype == FOCUS_F32)
