@@ -17,6 +17,10 @@
  *     until focus_free(), and must not touch the workspace in between.
  *   - focus_step / focus_select_compact / focus_commit only enqueue work on the given stream: no allocation,
  *     no host synchronisation; outputs are valid once the caller has synchronised the stream.
+ *   - HIP graphs: a step contains no memset or copy node of its own making, no allocation and no host synchronisation, and
+ *     every kernel reads the packed row count from device memory, so one captured step serves every later step whatever
+ *     the number of retained rows.  The first launch of some kernels in a process sets their dynamic-LDS attribute, which
+ *     is not a stream operation: run one step eagerly before capturing.
  *   - A context is not thread-safe.  The same calls on the same inputs give bitwise identical results
  *     (no floating-point atomics anywhere).
  *
