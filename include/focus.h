@@ -17,7 +17,8 @@
  *     until focus_free(), and must not touch the workspace in between.
  *   - focus_step / focus_select_compact / focus_commit only enqueue work on the given stream: no allocation,
  *     no host synchronisation; outputs are valid once the caller has synchronised the stream.
- *   - HIP graphs: a step contains no memset or copy node of its own making, no allocation and no host synchronisation, and
+ *   - HIP graphs: a step records no memset node (device-to-device copies only for the hidden-state outputs, when they are
+ *     asked for), allocates nothing and never synchronises with the host, and
  *     every kernel reads the packed row count from device memory, so one captured step serves every later step whatever
  *     the number of retained rows.  The first launch of some kernels in a process sets their dynamic-LDS attribute, which
  *     is not a stream operation: run one step eagerly before capturing.
