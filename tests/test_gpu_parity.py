@@ -282,6 +282,15 @@ def test_c1_moe_single_choice_without_shared_expert_and_intra_block_cache():
     compare_steps(wl, wl.steps, 1e-3, exact=True)
 
 
+def test_c1_everything_at_once_fp32_exact():
+    """Mixture of experts from layer 0, delayed intra-block cache, dynamic budget, both structural constraints, eviction
+    after layer 2: every switch of the step in one run."""
+    wl = fi.workload("c1_tiny", n_layers=4, evict_layer=2, first_moe_layer=0, intra_block_cache=1, conf_threshold=0.0013,
+                     budget_mode=2, alpha=1.5, constraints=3, steps=6, **MOE_TINY)
+    stats = compare_steps(wl, wl.steps, 1e-3, exact=True)
+    assert stats[-1]["frozen"] > 0, stats
+
+
 def small_bf16(**over):
     base = dict(n_layers=3, hidden=512, n_q_heads=8, n_kv_heads=2, ffn=1024, vocab=4096, mask_token_id=4095,
                 batch=5, prefix_lo=70, prefix_hi=200, prefix_dist="uniform", block_size=32, budget_mode=1,
