@@ -122,6 +122,8 @@ def compare_steps(wl, steps, tol, exact, seq_ids=None, k_override=None, forced_r
     for step in range(steps):
         print("step", step, flush=True)
         masked_before = [list(st.masked) for st in states]
+        pre = [(list(st.masked), list(st.processed), list(st.cached) if st.cached else [False] * B, st.token_sum, st.total_steps, st.slot)
+               for st in states]
         if wl.n_experts:
             outs.t["route_experts"].fill_(-1)
         sess.focus.focus_step(n, k_override=ko_dev, out=outs.struct)
@@ -138,7 +140,10 @@ def compare_steps(wl, steps, tol, exact, seq_ids=None, k_override=None, forced_r
         # scores
         e_dI = max(relerr(g["delta_I"][b], tr.delta_I[b]) for b in range(n))
         e_I = max(relerr(g["importance"][b], tr.I_evict[b]) for b in range(n))
-        assert e_I <= tol and e_dI <= max(tol, 5 * tol if not exact else tol), (e_I, e_dI)
+        # the delta is a difference of two importances that are each within the tolerance of their own scale: its error is
+        # bounded on that scale (relative to the delta's own size it can be anything when the two layers nearly agree)
+        a_dI = max(float(np.max(np.abs(g["delta_I"][b] - tr.delta_I[b]))) / max(float(np.max(np.abs(tr.I_evict[b]))), 1e-30) for b in range(n))
+        assert e_I <= tol and a_dI <= 2 * tol, (e_I, a_dI, e_dI)
         for b in range(n):      # Eq. 2 sums to (query rows) x H_q: all B positions, or those not frozen (Sec. 4.3)
             assert abs(float(g["importance"][b].sum()) - len(tr.uncached[b]) * wl.n_q_heads) < 1e-2 * B * wl.n_q_heads * tol + 1e-3
         # decisions
@@ -147,9 +152,17 @@ def compare_steps(wl, steps, tol, exact, seq_ids=None, k_override=None, forced_r
             assert keep_gpu == tr.keep
         else:
             for b in range(n):
+                # the integer logic on the GPU's own scores: budget and retained set must be exactly what the oracle's rules
+                # give for those fp32 values (whatever the switches); the scores themselves were compared above
                 Kb = int(g["K"][b])
-                scale = float(np.max(np.abs(tr.delta_I[b])))
-                check_selection_valid(tr.delta_I[b], masked_before[b], set(keep_gpu[b]), Kb, B, 5 * tol * scale)
+                d = g["delta_I"][b].astype(np.float64)
+                m, pr, ca, ts, tsteps, slot = pre[b]
+                assert Kb == fo.budget(cfg, d, m, ts, tsteps, None if k_override is None else k_override[b]), b
+                rk = [fo.selection_key(cfg.selection_seed, slot, tsteps, j) for j in range(B)] if cfg.selection == 1 else None
+                assert keep_gpu[b] == fo.select(cfg, d, m, pr, Kb, ca, rk), b
+                if cfg.constraints == 0 and not cfg.intra_block_cache and cfg.selection == 0:
+                    scale = float(np.max(np.abs(tr.delta_I[b])))
+                    check_selection_valid(tr.delta_I[b], masked_before[b], set(keep_gpu[b]), Kb, B, 5 * tol * scale)
         assert [int(x) for x in g["cu_seqlens"]] == tr.cu
         T = tr.cu[-1]
         assert [int(x) for x in g["row_map"][:T]] == tr.row_map
@@ -618,3 +631,45 @@ def test_run_steps_equals_separate_steps_with_finalisation(budget_mode, intra_bl
     assert decoded.cpu().numpy().tolist() == total.tolist()
     assert torch.equal(sess.kv_pool.cpu(), kv_want)
     sess.focus.focus_free()
+
+
+def _random_workload(seed, bf16):
+    """A small configuration drawn from the seed: shapes and switches that the fixed tests do not visit."""
+    r = np.random.default_rng(1000 + seed)
+    pick = lambda xs: xs[int(r.integers(0, len(xs)))]
+    n_layers = int(r.integers(2, 5))
+    importance_mode = pick([0, 0, 1])
+    evict = int(r.integers(1 if importance_mode == 0 else 0, n_layers))
+    B = pick([1, 2, 3, 8, 16, 31, 33, 64]) if not bf16 else pick([2, 5, 17, 32, 48, 64])
+    budget_mode = pick([0, 1, 1, 2])
+    over = dict(n_layers=n_layers, evict_layer=evict, importance_mode=importance_mode, maxpool_k=pick([1, 3]), block_size=B,
+                budget_mode=budget_mode, topk=int(r.integers(0, B + 1)), keep_ratio=float(pick([0.1, 0.25, 0.5, 0.75, 1.0])),
+                alpha=float(pick([1.0, 1.5, 2.5])), constraints=int(r.integers(0, 4)), intra_block_cache=pick([0, 1]),
+                conf_threshold=float(pick([0.9, 0.002, 0.0005])), batch=int(r.integers(1, 7)), steps=3,
+                selection=pick([0, 0, 1, 2]), selection_seed=int(r.integers(0, 1 << 30)))
+    if bf16:
+        hkv = pick([1, 2, 4, 8])
+        lo = int(r.integers(0, 150))
+        over.update(hidden=pick([256, 512]), n_q_heads=8, n_kv_heads=hkv, ffn=pick([256, 768]), vocab=4096, mask_token_id=4095,
+                    prefix_lo=lo, prefix_hi=lo + int(r.integers(0, 200)), prefix_dist="uniform", shuffle_pages=bool(r.integers(0, 2)))
+        return fi.workload("c3_llada36", **over)
+    hq = pick([2, 4, 8])
+    lo = int(r.integers(0, 40))
+    over.update(n_q_heads=hq, n_kv_heads=pick([h for h in (1, 2, 4, 8) if hq % h == 0]), head_dim=pick([64, 128]), hidden=pick([64, 256]),
+                ffn=pick([128, 320]), page_size=pick([16, 32, 64]), prefix_lo=lo, prefix_hi=lo + int(r.integers(0, 60)),
+                prefill=pick(["prompt", "synthetic"]), shuffle_pages=bool(r.integers(0, 2)))
+    return fi.workload("c1_tiny", **over)
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_small_configurations_fp32_exact(seed):
+    wl = _random_workload(seed, bf16=False)
+    print(wl, flush=True)
+    compare_steps(wl, wl.steps, 1e-3, exact=True)
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_small_configurations_bf16(seed):
+    wl = _random_workload(seed, bf16=True)
+    print(wl, flush=True)
+    compare_steps(wl, wl.steps, 2e-2, exact=False)
