@@ -471,9 +471,12 @@ def test_commit_stage_bit_exact():
     sess.focus.focus_free()
 
 
-def test_run_twice_bitwise_and_slot_permutation():
+@pytest.mark.parametrize("moe", [False, True])
+def test_run_twice_bitwise_and_slot_permutation(moe):
+    """Same call, same bits; and a permuted batch order moves the rows without changing a bit of them (with experts: the rows
+    then sit in other tiles of the grouped projections, next to other rows)."""
     pk, runner = _pk()
-    wl = small_bf16(batch=4, steps=1)
+    wl = small_bf16(batch=4, steps=1, **(dict(first_moe_layer=0, **MOE_SMALL) if moe else {}))
     res = []
     for perm in (None, None, [2, 0, 3, 1]):
         sess = runner.open_session(wl, DEV)
