@@ -304,6 +304,16 @@ def test_c1_everything_at_once_fp32_exact():
     assert stats[-1]["frozen"] > 0, stats
 
 
+def test_no_prefix_and_single_sequence():
+    """A block with nothing before it (the attention sees the block alone) and a batch of one.  Without a prefix all rows are
+    the mask token and differ by their position only, so confidences come out nearly equal: decisions are checked for validity
+    within the tolerance there, not for identity."""
+    compare_steps(fi.workload("c1_tiny", prefix_lo=0, prefix_hi=0, prefix_dist="fixed", steps=3), 3, 1e-3, exact=False)
+    compare_steps(fi.workload("c1_tiny", batch=1, steps=2), 2, 1e-3, exact=True)
+    compare_steps(small_bf16(prefix_lo=0, prefix_hi=0, prefix_dist="fixed", batch=2, steps=2), 2, 2e-2, exact=False)
+    compare_steps(small_bf16(batch=1, steps=2), 2, 2e-2, exact=False)
+
+
 def small_bf16(**over):
     base = dict(n_layers=3, hidden=512, n_q_heads=8, n_kv_heads=2, ffn=1024, vocab=4096, mask_token_id=4095,
                 batch=5, prefix_lo=70, prefix_hi=200, prefix_dist="uniform", block_size=32, budget_mode=1,
