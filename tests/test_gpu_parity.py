@@ -520,7 +520,7 @@ def test_step_argument_errors():
         sess.focus.focus_prefill_kv([10_000], [[0]])       # prefix longer than planned
     with pytest.raises(pk.FocusError):
         sess.focus.focus_prefill_kv([8], [[999]])          # page outside the pool
-    sess.focus.focus_step(0)                               # an empty batch is a no-op
+    sess.focus.focus_step(0, k_override=torch.zeros(1, dtype=torch.int32, device=DEV))   # an empty batch is a no-op
     sess.focus.focus_finalize_blocks(0)
     with pytest.raises(pk.FocusError):
         sess.focus.focus_run_steps(wl.batch, 2)            # per-step budgets cannot be looped
