@@ -235,6 +235,30 @@ def main():
         b_.copy_(a_)
         torch.cuda.synchronize()
 
+    # achievable ceilings measured in the same run: a device copy for HBM, the vendor library's bf16 GEMM on the gate/up shape as
+    # an outside yardstick for the matrix cores (torch.matmul; nothing of it is linked into the library)
+    def timed_ms(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")
+    dst = torch.empty_like(src)
+    src.fill_(1)
+    copy_ms = timed_ms(lambda: dst.copy_(src), 5)
+    ga = torch.randn(2048, wl.hidden, device="cuda:0").to(torch.bfloat16)
+    gw = (torch.randn(2 * wl.ffn, wl.hidden, device="cuda:0") * 0.02).to(torch.bfloat16)
+    mm_ms = timed_ms(lambda: torch.matmul(ga, gw.t()), 10)
+    ceilings = dict(hbm_copy_GBs=round(2.0 * (1 << 30) / (copy_ms * 1e-3) / 1e9, 1),
+                    library_gemm_TFLOPs=round(2.0 * 2048 * 2 * wl.ffn * wl.hidden / (mm_ms * 1e-3) / 1e12, 1),
+                    note="1 GiB device-to-device copy (read + write bytes); torch.matmul bf16 2048 x %d x %d with random operands" % (2 * wl.ffn, wl.hidden))
+    del src, dst, ga, gw
+
     sweep = None
     if args.sweep:
         sweep = [head] + [run(r, args.steps, args.warmup) for r in (1.0, 0.5, 0.125) if abs(r - ratio0) > 1e-9 and wl.budget_mode == 1]
@@ -255,7 +279,7 @@ def main():
                    "experts": None if not wl.n_experts else "%d experts x %d, %d per token, shared %d, dense below layer %d"
                               % (wl.n_experts, wl.expert_ffn, wl.experts_per_token, wl.shared_ffn, wl.first_moe_layer),
                    "debug_overrides": {k: v for k, v in (("layers", args.layers), ("batch", args.batch)) if v}},
-        "roofline": roofline, "dense_gemm": dense_gemm, "attention_hbm": attention, "kernel_classes_ms": classes, "cpu_baseline": cpu, "sweep": sweep,
+        "roofline": roofline, "dense_gemm": dense_gemm, "attention_hbm": attention, "kernel_classes_ms": classes, "ceilings": ceilings, "cpu_baseline": cpu, "sweep": sweep,
         "setup_s": round(t_setup, 1),
     }
     print(json.dumps(line))
