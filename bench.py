@@ -215,6 +215,15 @@ def main():
                     unit="TFLOP/s", frac=round(achieved / PEAK_BF16_TFLOPS, 4), traffic=traffic,
                     flops_per_step=flops, launches=classes["gemm"]["launches"], avg_launch_ms=round(gemm_ms / max(1, classes["gemm"]["launches"]), 5))
     dense_gemm = None
+    if not wl.n_experts and n * B < 312:
+        # fewer rows than the ridge point (about 312 flop per byte): the projections are bound by streaming every weight once
+        dense_gemm = roofline
+        qkv_w = (wl.n_q_heads + 2 * wl.n_kv_heads) * wl.head_dim
+        wbytes = 2.0 * (wl.n_layers * (qkv_w * wl.hidden + wl.n_q_heads * wl.head_dim * wl.hidden + 3 * wl.ffn * wl.hidden) + wl.vocab * wl.hidden)
+        gbs = wbytes / (gemm_ms * 1e-3) / 1e9 if gemm_ms > 0 else 0.0
+        roofline = dict(bound="hbm", kernel="gemm (all dense projections of a step; every weight is read once)", achieved=round(gbs, 1),
+                        peak=PEAK_HBM_GBS, unit="GB/s", frac=round(gbs / PEAK_HBM_GBS, 4), traffic=None, bytes_per_step=wbytes,
+                        launches=classes["gemm"]["launches"], avg_launch_ms=round(gemm_ms / max(1, classes["gemm"]["launches"]), 5))
     if wl.n_experts:
         # mixture-of-experts model: the grouped expert projections stream the expert weights once per layer and dominate
         dense_gemm = roofline
