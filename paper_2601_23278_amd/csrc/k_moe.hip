@@ -5,8 +5,8 @@
 // With k of E experts per row and a few thousand rows per step an expert sees a few dozen rows, so the grouped
 // projections are bound by streaming the expert weights from HBM once, not by the matrix cores: the kernel keeps two
 // K-slabs of weights in flight per workgroup and two workgroups per CU (LDS stages filled by direct-to-LDS loads), and
-// the matrix work hides underneath.  Everything is deterministic: entries are placed by prefix sums, never by atomics, and a row's result
-// does not depend on which other rows share its tile.
+// the matrix work hides underneath.  Everything is deterministic: entries are placed by prefix sums, never in the order
+// atomics happen to arrive, and a row's result does not depend on which other rows share its tile.
 #include <algorithm>
 
 #include "focus_internal.h"
@@ -168,9 +168,11 @@ void moe_group(hipStream_t s, const MoeArgs &a) {
 // three stages for the weights (two slabs in flight: they come from HBM), two for the rows (one in flight: they come
 // from the L2), 80 KB in all, so two workgroups share a CU and one streams while the other starts or stores.
 // Rows beyond the expert's count and weight rows beyond N fall outside the buffer descriptors and read as zero.
-//   GATE_UP: W = [Fe gate rows; Fe up rows] per expert; LDS weight rows 64 c .. 64 c + 31 are the gate rows of output
-//            columns 32 c .., the next 32 the matching up rows; out[bf16][row, col] = silu(gate) * up.
-//   else:    out[f32][row, col] = acc.
+//   GG_GATE_UP: W = [Fe gate rows; Fe up rows] per expert; LDS weight rows 64 c .. 64 c + 31 are the gate rows of output
+//               columns 32 c .., the next 32 the matching up rows; out[bf16][row, col] = silu(gate) * up.
+//   GG_DOWN:    out[f32][row, col] = acc.
+//   GG_DENSE_PARTIAL, GG_DENSE_PARTIAL_SILU: the same stream for a dense projection of few rows: one weight matrix, rows in
+//               place, K cut into `splits` ranges of which a workgroup takes one; fp32 partial sums out (gemm_stream_partial).
 struct GroupGemm {
   const bf16_t *A;
   unsigned a_bytes;            // size of A (for the descriptor)
