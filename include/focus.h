@@ -20,7 +20,10 @@
  *   - HIP graphs: a step records no memset node (device-to-device copies only for the hidden-state outputs, when they are
  *     asked for), allocates nothing and never synchronises with the host, and
  *     every kernel reads the packed row count from device memory, so one captured step serves every later step whatever
- *     the number of retained rows.  The first launch of some kernels in a process sets their dynamic-LDS attribute, which
+ *     the number of retained rows.  The K/V split geometry of the attention launches is fixed at capture from the
+ *     longest prefix installed then; the kernels read the real lengths on the device and the last split of a sequence
+ *     takes whatever lies beyond, so a replay stays correct after prefixes have grown (focus_finalize_blocks), up to
+ *     max_prefix_len, with the split sizes of the capture.  The first launch of some kernels in a process sets their dynamic-LDS attribute, which
  *     is not a stream operation: run one step eagerly before capturing.
  *   - A context is not thread-safe.  The same calls on the same inputs give bitwise identical results
  *     (no floating-point atomics anywhere).

@@ -100,10 +100,13 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_mfma(AttnArgs a) {
   if (nr <= 0) return;
   const int slot = slot_of(a.ri.seq_slot, b, a.st);
   const int L = a.st.prefix_len[slot], total = L + a.ri.B;
+  // Splits that have tokens: the sequence's own length decides (it is read here, on the device), bounded by the number of
+  // split workgroups this launch has; the last one takes everything that is left.  So a launch whose geometry was fixed when
+  // the prefixes were shorter (a captured graph replayed after blocks became prefix) still attends to every token.
+  const int nsplit = min((total + a.chunk - 1) / a.chunk, (int)gridDim.y);
+  if (split >= nsplit) return;
   const int t0 = split * a.chunk;
-  if (t0 >= total) return;
-  const int t1 = min(t0 + a.chunk, total);
-  const int nsplit = (total + a.chunk - 1) / a.chunk;
+  const int t1 = split == nsplit - 1 ? total : t0 + a.chunk;
   const uint64_t vis = a.vis_by_b ? a.vis_by_b[b] : ~0ull;
   const int32_t *pt = a.st.page_table + (size_t)slot * a.st.table_stride;
   const int R = min(nr * g, NW * 32);
@@ -299,7 +302,7 @@ __global__ __launch_bounds__(128) void k_attn_combine(AttnArgs a) {
   const int b = a.ri.row_map[r] / a.ri.B;
   const int slot = slot_of(a.ri.seq_slot, b, a.st);
   const int total = a.st.prefix_len[slot] + a.ri.B;
-  const int nsplit = (total + a.chunk - 1) / a.chunk;
+  const int nsplit = min((total + a.chunk - 1) / a.chunk, a.max_splits);   // as in k_attn_mfma
   if (nsplit <= 1) return;
   const size_t pi = ((size_t)r * a.n_q_heads + hq) * a.max_splits;
   float mm = -INFINITY;
