@@ -200,6 +200,29 @@ int focus_step(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32_t *s
 int focus_select_compact(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32_t *seq_slot,
                          const float *delta_I, const int32_t *k_override, const focus_step_out *out);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc) and that hold no context: the same budget + selection + packing as focus_select_compact, on caller-given
+ * scores AND caller-given block state, enqueued on the stream.  It calls no hipMalloc / hipFree and needs no workspace: its
+ * scratch (per-sequence retained counts and the packed total) is a fixed array inside the library, one copy per GPU held
+ * until the process ends (FOCUS_NOALLOC_MAX_SEQ + 64 ints = 64.25 KB).  Every call on a GPU uses that one array: calls
+ * that overlap on one GPU (two streams, two threads) race; calls on one stream are ordered and fine.  The array keeps
+ * the last call's contents; nothing in it has to start at zero.
+ *   cfg           only block_size, budget_mode, topk, keep_ratio, alpha, constraints, intra_block_cache, selection and
+ *                 selection_seed are read
+ *   n_seq         0..FOCUS_NOALLOC_MAX_SEQ, EINVAL beyond
+ *   delta_I       device [n_seq, B] fp32
+ *   mask_bits     device [n_seq] still-masked positions of batch entry b
+ *   cached_bits   device [n_seq] frozen positions (intra_block_cache), else may be NULL
+ *   token_sum, total_steps  device [n_seq] running statistics (FOCUS_BUDGET_DYNAMIC; total_steps also for
+ *                 FOCUS_SELECT_RANDOM, whose keys take the batch index as the slot), else may be NULL
+ *   k_override    device [n_seq] for FOCUS_BUDGET_OVERRIDE, else NULL
+ *   out           K, keep_bits, cu_seqlens, row_map are required and written; nothing else is touched
+ * Errors are reported through focus_last_error(NULL). */
+#define FOCUS_NOALLOC_MAX_SEQ 16384
+int focus_select_compact_noalloc(const focus_config *cfg, void *hip_stream, int32_t n_seq, const float *delta_I,
+                                 const uint64_t *mask_bits, const uint64_t *cached_bits, const int64_t *token_sum,
+                                 const int32_t *total_steps, const int32_t *k_override, const focus_step_out *out);
+
 /* Stage entry: runs layers [layer_begin, layer_end) of the reduced forward pass (Alg. 1 phase 3, "Forward(H_reduced,
  * C, Layers = 1_suffix ... L)") on caller-given hidden states, so that deep layers can be compared with a
  * reference fed the same input.  layer_begin must be above the eviction layer.  Rows are the positions in

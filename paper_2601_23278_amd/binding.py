@@ -76,6 +76,7 @@ def load_library() -> C.CDLL:
         "focus_prefill_kv": [P, P, I, C.POINTER(I), C.POINTER(I), C.POINTER(I), I, C.POINTER(I), I],
         "focus_step": [P, P, I, P, P, P, C.POINTER(focus_step_out)],
         "focus_select_compact": [P, P, I, P, P, P, C.POINTER(focus_step_out)],
+        "focus_select_compact_noalloc": [C.POINTER(focus_config), P, I, P, P, P, P, P, P, C.POINTER(focus_step_out)],
         "focus_commit": [P, P, I, P, P, P, P, P, C.POINTER(focus_step_out)],
         "focus_run_layers": [P, P, I, P, P, P, I, I, P],
         "focus_finalize_blocks": [P, P, I, P, P],
@@ -96,7 +97,7 @@ def load_library() -> C.CDLL:
 
 _lib = load_library()
 EXPORTS = ["focus_workspace_bytes", "focus_kv_pool_bytes", "focus_init", "focus_prefill_kv", "focus_step",
-           "focus_select_compact", "focus_commit", "focus_run_layers", "focus_finalize_blocks", "focus_set_route_override", "focus_run_steps", "focus_get_state", "focus_set_state", "focus_set_timing",
+           "focus_select_compact", "focus_select_compact_noalloc", "focus_commit", "focus_run_layers", "focus_finalize_blocks", "focus_set_route_override", "focus_run_steps", "focus_get_state", "focus_set_state", "focus_set_timing",
            "focus_get_kernel_time", "focus_free", "focus_last_error"]
 
 
@@ -123,6 +124,18 @@ def focus_kv_pool_bytes(cfg: focus_config) -> int:
     n = C.c_size_t()
     _check(_lib.focus_kv_pool_bytes(C.byref(cfg), C.byref(n)))
     return n.value
+
+
+FOCUS_NOALLOC_MAX_SEQ = 16384
+
+
+def focus_select_compact_noalloc(cfg: focus_config, n_seq: int, delta_I: torch.Tensor, mask_bits: torch.Tensor,
+                                 out: "focus_step_out", cached_bits: Optional[torch.Tensor] = None,
+                                 token_sum: Optional[torch.Tensor] = None, total_steps: Optional[torch.Tensor] = None,
+                                 k_override: Optional[torch.Tensor] = None, stream=None):
+    _check(_lib.focus_select_compact_noalloc(C.byref(cfg), Focus._stream(stream), n_seq, _ptr(delta_I), _ptr(mask_bits),
+                                             _ptr(cached_bits), _ptr(token_sum), _ptr(total_steps), _ptr(k_override),
+                                             C.byref(out)))
 
 
 def make_step_out(**tensors) -> focus_step_out:

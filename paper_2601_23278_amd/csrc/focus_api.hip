@@ -14,6 +14,14 @@ namespace {
 
 std::string g_error;   // last error of a call that had no context
 
+// Scratch of focus_select_compact_noalloc: per-sequence retained counts and the packed row total.  One copy per GPU, held
+// until the process ends.  In host code the array's name is only a handle for hipGetSymbolAddress: the device address of
+// each GPU's copy is looked up once per device (scratch_of_current_device) and that pointer is what kernels get.
+constexpr int kNoallocScratchInts = FOCUS_NOALLOC_MAX_SEQ + 64;
+static __device__ __align__(256) int32_t scratch[kNoallocScratchInts];
+constexpr int kMaxDevices = 64;
+int32_t *g_scratch_ptr[kMaxDevices];
+
 constexpr int kMaxTimed = 4096;
 constexpr int kTargetAttnGroups = 2048;   // (sequence, kv head, split) workgroups the attention launch aims for
 
@@ -200,6 +208,27 @@ int fail(focus_ctx *ctx, int code, const char *fmt, ...) {
     hipError_t e_ = (expr);                                                                        \
     if (e_ != hipSuccess) return fail(ctx, FOCUS_EHIP, "%s: %s", #expr, hipGetErrorString(e_));    \
   } while (0)
+
+// Device address of the current GPU's copy of `scratch`, looked up on the first call per device (focus_init does it for the
+// device a context is created on).  Null with the error stored when the lookup fails.
+int32_t *scratch_of_current_device(focus_ctx *ctx) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    fail(ctx, FOCUS_EHIP, "hipGetDevice: %s (device %d)", hipGetErrorString(e), dev);
+    return nullptr;
+  }
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) {
+      fail(ctx, FOCUS_EHIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = (int32_t *)p;
+  }
+  return g_scratch_ptr[dev];
+}
 
 // Brackets the launches of one kernel class with an event pair when timing is on.
 struct Timed {
@@ -451,6 +480,10 @@ int focus_init(const focus_config *cfg, const focus_weights *w, void *kv_pool, s
     int rc = fail(nullptr, FOCUS_EHIP, "focus_init: %s", hipGetErrorString(e));
     delete c;
     return rc;
+  }
+  if (!scratch_of_current_device(nullptr)) {   // set-up for focus_select_compact_noalloc on this device
+    delete c;
+    return FOCUS_EHIP;
   }
   *out = c;
   return FOCUS_OK;
@@ -736,6 +769,49 @@ int focus_select_compact(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const 
   fk::select(s, a);
   fk::scan_compact(s, n_seq, g.block_size, out->keep_bits, out->cu_seqlens, out->row_map, ctx->at<int32_t>(ctx->plan.off_total));
   HIP_TRY(ctx, hipGetLastError());
+  return FOCUS_OK;
+}
+
+int focus_select_compact_noalloc(const focus_config *cfg, void *hip_stream, int32_t n_seq, const float *delta_I,
+                                 const uint64_t *mask_bits, const uint64_t *cached_bits, const int64_t *token_sum,
+                                 const int32_t *total_steps, const int32_t *k_override, const focus_step_out *out) {
+  if (!cfg || !delta_I || !mask_bits || !out || !out->K || !out->keep_bits || !out->cu_seqlens || !out->row_map)
+    return fail(nullptr, FOCUS_EINVAL, "cfg, delta_I, mask_bits and out->K, keep_bits, cu_seqlens, row_map are required");
+  const focus_config &g = *cfg;
+  if (g.block_size < 1 || g.block_size > FOCUS_MAX_BLOCK) return fail(nullptr, FOCUS_EINVAL, "block_size must be in 1..64");
+  if (g.budget_mode < 0 || g.budget_mode > 3 || (g.constraints & ~3) || (g.intra_block_cache & ~1) ||
+      g.selection < FOCUS_SELECT_TOP || g.selection > FOCUS_SELECT_BOTTOM)
+    return fail(nullptr, FOCUS_EINVAL, "unknown budget_mode, constraint bits, intra_block_cache or selection");
+  if (n_seq < 0 || n_seq > FOCUS_NOALLOC_MAX_SEQ)
+    return fail(nullptr, FOCUS_EINVAL, "n_seq %d outside 0..FOCUS_NOALLOC_MAX_SEQ (%d)", n_seq, FOCUS_NOALLOC_MAX_SEQ);
+  if (n_seq == 0) return FOCUS_OK;
+  if (g.budget_mode == FOCUS_BUDGET_OVERRIDE && !k_override) return fail(nullptr, FOCUS_EINVAL, "budget_mode OVERRIDE needs k_override");
+  if (g.budget_mode == FOCUS_BUDGET_DYNAMIC && (!token_sum || !total_steps)) return fail(nullptr, FOCUS_EINVAL, "budget_mode DYNAMIC needs token_sum and total_steps");
+  if (g.selection == FOCUS_SELECT_RANDOM && !total_steps) return fail(nullptr, FOCUS_EINVAL, "selection RANDOM needs total_steps");
+  if (g.intra_block_cache && !cached_bits) return fail(nullptr, FOCUS_EINVAL, "intra_block_cache needs cached_bits");
+  int32_t *sc = scratch_of_current_device(nullptr);
+  if (!sc) return FOCUS_EHIP;
+  hipStream_t s = (hipStream_t)hip_stream;
+  // the caller's arrays stand in for the slot state, batch entry b = slot b; nothing of it is written
+  fk::SlotState st{};
+  st.mask_bits = const_cast<uint64_t *>(mask_bits);
+  st.cached_bits = const_cast<uint64_t *>(cached_bits);
+  st.token_sum = const_cast<int64_t *>(token_sum);
+  st.total_steps = const_cast<int32_t *>(total_steps);
+  st.max_batch = n_seq;
+  fk::SelectArgs a{};
+  a.n_seq = n_seq; a.B = g.block_size; a.n_q_heads = g.n_q_heads;
+  a.delta_in = delta_I;
+  a.importance_mode = g.importance_mode; a.budget_mode = g.budget_mode; a.K_fixed = fixed_budget(g);
+  a.constraints = g.constraints; a.alpha = g.alpha; a.k_override = k_override; a.keep_override = nullptr;
+  a.seq_slot = nullptr; a.st = st; a.update_state = 0; a.intra_block_cache = g.intra_block_cache;
+  a.selection = g.selection; a.selection_seed = g.selection_seed;
+  a.delta_out = nullptr; a.K_out = out->K; a.keep_out = out->keep_bits;
+  a.n_keep_out = sc; a.vis_out = nullptr;                     // scratch: [0, n_seq) retained counts, [MAX_SEQ] packed total
+  fk::select(s, a);
+  fk::scan_compact(s, n_seq, g.block_size, out->keep_bits, out->cu_seqlens, out->row_map, sc + FOCUS_NOALLOC_MAX_SEQ);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(nullptr, FOCUS_EHIP, "focus_select_compact_noalloc: %s", hipGetErrorString(e));
   return FOCUS_OK;
 }
 

@@ -124,9 +124,11 @@ __global__ __launch_bounds__(64) void k_select(SelectArgs a) {
     a.K_out[b] = K;
     a.keep_out[b] = keep;
     a.n_keep_out[b] = __popcll(keep);
-    uint64_t proc = a.st.processed_bits[slot] | keep;
-    if (a.update_state) a.st.processed_bits[slot] = proc;
-    if (a.vis_out) a.vis_out[b] = proc;
+    if (a.update_state || a.vis_out) {
+      const uint64_t proc = a.st.processed_bits[slot] | keep;
+      if (a.update_state) a.st.processed_bits[slot] = proc;
+      if (a.vis_out) a.vis_out[b] = proc;
+    }
   }
 }
 
