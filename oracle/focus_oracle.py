@@ -86,6 +86,14 @@ class OracleConfig:
     shared_ffn: int = 0           # F_s, inner width of the always-on shared expert; 0 = none
     first_moe_layer: int = 0      # layers below it keep the dense feed-forward
     route_scale: float = 1.0      # factor on the routed experts' sum
+    # Optional model of a reduced-precision activation format.  None (the default) leaves every value in float64: that is
+    # the oracle.  A function (name, array) -> array is applied where an implementation that keeps activations in the
+    # model's 16-bit type (the benchmark configurations fix bf16) has to round them: "normed" (RMSNorm output, the operand
+    # of a projection), "qkv" (projection output), "rope" (rotated q and k), "p" (un-normalised softmax probabilities as the
+    # operand of P V), "attn" (attention output), "act" (SiLU(gate) * up).  The residual stream, the softmax statistics and
+    # the logits are never passed through it.  Used by oracle/drift_study.py and by the end-to-end parity tests of the
+    # bf16 configurations to tell format rounding from implementation error.
+    store_cast: Optional[Callable] = None
 
 
 @dataclass
@@ -382,6 +390,10 @@ def commit(cfg: OracleConfig, st: SeqState, S: Sequence[int], conf: Sequence[flo
 # ---------------------------------------------------------------------------------------------
 # transformer layer on a set of rows
 
+def _cast(cfg: OracleConfig, name: str, x: np.ndarray) -> np.ndarray:
+    return x if cfg.store_cast is None else cfg.store_cast(name, x)
+
+
 def _attention(cfg: OracleConfig, q: np.ndarray, K: np.ndarray, V: np.ndarray) -> np.ndarray:
     """q [r, H_q, D] over keys/values [t, H_kv, D]: one ordinary softmax per (row, head) over all t
     keys (prefix and visible block positions alike; no mask inside the block)."""
@@ -390,25 +402,31 @@ def _attention(cfg: OracleConfig, q: np.ndarray, K: np.ndarray, V: np.ndarray) -
     out = np.empty((r, Hq, D))
     for h in range(Hq):
         S = q[:, h, :] @ K[:, h // g, :].T / math.sqrt(D)
-        out[:, h, :] = softmax_rows(S) @ V[:, h // g, :]
-    return out
+        if cfg.store_cast is None:
+            out[:, h, :] = softmax_rows(S) @ V[:, h // g, :]
+        else:       # format model: the probabilities are rounded as an operand, their sum is not
+            E = np.exp(S - np.max(S, axis=-1, keepdims=True))
+            out[:, h, :] = (cfg.store_cast("p", E) @ V[:, h // g, :]) / np.sum(E, axis=-1, keepdims=True)
+    return _cast(cfg, "attn", out)
 
 
 def _project_qkv(cfg: OracleConfig, w: Dict[str, np.ndarray], X: np.ndarray, abs_pos: np.ndarray):
-    u = rmsnorm(X, w["attn_norm"], cfg.rms_eps)
-    qkv = u @ w["w_qkv"].T
+    u = _cast(cfg, "normed", rmsnorm(X, w["attn_norm"], cfg.rms_eps))
+    qkv = _cast(cfg, "qkv", u @ w["w_qkv"].T)
     Hq, Hkv, D = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
     q = qkv[:, :Hq * D].reshape(-1, Hq, D)
     k = qkv[:, Hq * D:(Hq + Hkv) * D].reshape(-1, Hkv, D)
     v = qkv[:, (Hq + Hkv) * D:].reshape(-1, Hkv, D)
-    return rope(q, abs_pos, cfg.rope_base), rope(k, abs_pos, cfg.rope_base), v
+    return _cast(cfg, "rope", rope(q, abs_pos, cfg.rope_base)), _cast(cfg, "rope", rope(k, abs_pos, cfg.rope_base)), v
 
 
-def swiglu(u: np.ndarray, w_gate_up: np.ndarray, w_down: np.ndarray) -> np.ndarray:
-    """SwiGLU feed-forward: (silu(u Wg^T) * (u Wu^T)) Wd^T with w_gate_up = [Wg; Wu] stacked by rows."""
+def swiglu(u: np.ndarray, w_gate_up: np.ndarray, w_down: np.ndarray, act_cast=None) -> np.ndarray:
+    """SwiGLU feed-forward: (silu(u Wg^T) * (u Wu^T)) Wd^T with w_gate_up = [Wg; Wu] stacked by rows.
+    act_cast: optional format model applied to silu(gate) * up (OracleConfig.store_cast)."""
     F = w_gate_up.shape[0] // 2
     gu = u @ w_gate_up.T
-    return (silu(gu[:, :F]) * gu[:, F:]) @ w_down.T
+    act = silu(gu[:, :F]) * gu[:, F:]
+    return (act if act_cast is None else act_cast("act", act)) @ w_down.T
 
 
 def route(cfg: OracleConfig, logits: np.ndarray, forced: Optional[Sequence[int]] = None):
@@ -442,9 +460,9 @@ def moe_ffn(cfg: OracleConfig, w: Dict[str, np.ndarray], u: np.ndarray, forced=N
         experts.append(ch)
         weights.append(wt)
         for e, g in zip(ch, wt):
-            y[i] += g * swiglu(u[i:i + 1], w["w_expert_gate_up"][e], w["w_expert_down"][e])[0]
+            y[i] += g * swiglu(u[i:i + 1], w["w_expert_gate_up"][e], w["w_expert_down"][e], cfg.store_cast)[0]
     if cfg.shared_ffn > 0:
-        y += swiglu(u, w["w_shared_gate_up"], w["w_shared_down"])
+        y += swiglu(u, w["w_shared_gate_up"], w["w_shared_down"], cfg.store_cast)
     return y, experts, weights, logits
 
 
@@ -453,7 +471,7 @@ def _finish_layer(cfg: OracleConfig, w: Dict[str, np.ndarray], X: np.ndarray, at
     """Output projection, residual, then the feed-forward (dense, or mixture-of-experts from first_moe_layer on) and its
     residual.  row_ids[i] = b * B + p names row i for route_override[layer][row id] and for route_log[layer]."""
     X = X + attn.reshape(X.shape[0], cfg.n_q_heads * cfg.head_dim) @ w["w_o"].T      # explicit width: a step may have no rows
-    u = rmsnorm(X, w["mlp_norm"], cfg.rms_eps)
+    u = _cast(cfg, "normed", rmsnorm(X, w["mlp_norm"], cfg.rms_eps))
     if cfg.n_experts > 0 and layer >= cfg.first_moe_layer:
         forced = None if route_override is None else [route_override[layer][rid] for rid in row_ids]
         y, experts, weights, logits = moe_ffn(cfg, w, u, forced)
@@ -461,7 +479,7 @@ def _finish_layer(cfg: OracleConfig, w: Dict[str, np.ndarray], X: np.ndarray, at
             for i, rid in enumerate(row_ids):
                 route_log.setdefault(layer, {})[rid] = (experts[i], weights[i], logits[i])
         return X + y
-    return X + swiglu(u, w["w_gate_up"], w["w_down"])
+    return X + swiglu(u, w["w_gate_up"], w["w_down"], cfg.store_cast)
 
 
 @dataclass
@@ -612,7 +630,7 @@ def focus_step(cfg: OracleConfig, W: Weights, pool: KVPool, seqs: List[SeqState]
     tr.hidden_packed = Xp
 
     # decode and verify
-    logits = rmsnorm(Xp, W.final_norm, cfg.rms_eps) @ W.lm_head.T
+    logits = _cast(cfg, "normed", rmsnorm(Xp, W.final_norm, cfg.rms_eps)) @ W.lm_head.T
     tr.logits = logits
     conf, am = confidence(logits) if len(rows) else (np.zeros(0), np.zeros(0, dtype=np.int64))
     tr.conf = conf_cast(conf) if conf_cast is not None else conf

@@ -90,3 +90,59 @@ def oracle_batch(wl: Workload, seq_ids: Optional[Sequence[int]] = None, lazy_emb
         prompts = wl.prompt_tokens(lens)
         fo.prefill(cfg, W, pool, states, [prompts[b] for b in ids])
     return cfg, W, pool, states, lens, tables, n_pages
+
+
+def round_bf16(x: np.ndarray) -> np.ndarray:
+    """Round to nearest-even bf16, returned as float64 (the format model of OracleConfig.store_cast)."""
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(x)).to(torch.float32).to(torch.bfloat16).to(torch.float64).numpy()
+
+
+BF16_STORE_POINTS = ("normed", "qkv", "rope", "p", "attn", "act")
+
+
+def bf16_store_cast(points: Sequence[str] = BF16_STORE_POINTS):
+    """store_cast that rounds the named activation stores to bf16 and leaves the rest in float64."""
+    pts = set(points)
+    return lambda name, x: round_bf16(x) if name in pts else x
+
+
+def oracle_weights_from_tensors(wl: Workload, lm_head, layers, max_cached_bytes: float = 8e10) -> fo.Weights:
+    """Float64 weights widened from already generated tensors of the workload (any device; e.g. the ones a GPU test
+    generated with the same seeded recipe, which saves generating 16 GB a second time on the host).  A widened layer
+    is kept for later passes over the model while the kept layers stay below max_cached_bytes."""
+    cache: Dict[int, Dict[str, np.ndarray]] = {}
+    used = [0.0]
+    ones = np.ones(wl.hidden)
+
+    def layer(l: int):
+        if l in cache:
+            return cache[l]
+        w = {k: _f64(v.cpu()) for k, v in layers[l].items() if k.startswith("w_") and not k.startswith("w_expert")}
+        for k, v in layers[l].items():
+            if k.startswith("w_expert"):
+                w[k] = LazyExperts(v)
+        w["attn_norm"] = ones
+        w["mlp_norm"] = ones
+        size = sum(a.nbytes for a in w.values() if isinstance(a, np.ndarray))
+        if used[0] + size <= max_cached_bytes:
+            cache[l] = w
+            used[0] += size
+        return w
+
+    return fo.Weights(LazyRows(wl), _f64(lm_head.cpu()), ones, layer)
+
+
+class LazyExperts:
+    """Per-expert weight stack [E, ...] whose experts are widened to float64 when they are indexed (a step touches a few
+    experts of the hundreds a mixture-of-experts layer has)."""
+
+    def __init__(self, t):
+        self.t = t
+        self.cache: Dict[int, np.ndarray] = {}
+
+    def __getitem__(self, e):
+        e = int(e)
+        if e not in self.cache:
+            self.cache[e] = _f64(self.t[e].cpu())
+        return self.cache[e]

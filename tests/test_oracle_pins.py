@@ -904,3 +904,46 @@ def test_step_with_identical_experts_equals_the_dense_model(first):
         assert sorted(tm.route) == list(range(first, 3)) and all(len(v[0]) == 2 for v in tm.route[2].values())
         assert first or len(tm.route[0]) == 2 * moe.block_size           # layers below e run on the whole block
         assert set(tm.route[2]) == set(tm.row_map) == set(tm.route[1])      # the feed-forward of layer e runs after the gather
+
+
+# ---------------------------------------------------------------------------------------------
+# freeze criterion of the delayed intra-block cache: a hand-worked trace (tests/golden/r17_freeze_trace.txt)
+
+def test_intra_block_cache_freeze_trace_worked_by_hand():
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "r17_freeze_trace.txt")) if l.strip() and not l.startswith("#")]
+    assert len(rows) == 4
+    B = 6
+    as_set = lambda s: set() if s == "-" else {int(c) for c in s}
+    cfg = tiny_cfg(n_layers=3, block_size=B, intra_block_cache=1, conf_threshold=2.0)     # threshold above 1: only forced commits
+    W = tiny_weights(cfg, seed=5)
+    pool, states, _ = tiny_batch(cfg, W, [9], seed=3)
+    st = states[0]
+    for masked, S, before, after in rows:
+        M, S, C0, C1 = as_set(masked), sorted(as_set(S)), as_set(before), as_set(after)
+        assert st.cached == [p in C0 for p in range(B)]           # the trace's steps chain: what a step froze is the next one's input
+        st.masked = [p in M for p in range(B)]
+        st.tokens = [cfg.mask_token_id if p in M else 1 + p for p in range(B)]
+        tr = fo.focus_step(cfg, W, pool, states, keep_override=[S])
+        assert tr.uncached[0] == [p for p in range(B) if p not in C0]
+        assert st.cached == [p in C1 for p in range(B)], (masked, S, st.cached)
+
+
+# ---------------------------------------------------------------------------------------------
+# storage-format model (OracleConfig.store_cast): off = the oracle; identity = the oracle (pins the un-normalised softmax
+# form it uses); bf16 = a small, non-zero distance
+
+def test_store_cast_identity_is_the_oracle_and_bf16_is_close():
+    from oracle.harness import bf16_store_cast, round_bf16
+    outs = {}
+    for name, cast in (("off", None), ("identity", lambda n, x: x), ("bf16", bf16_store_cast())):
+        cfg = tiny_cfg(n_layers=3, keep_ratio=0.5)
+        cfg.store_cast = cast
+        W = tiny_weights(cfg, seed=41)
+        pool, states, _ = tiny_batch(fo.OracleConfig(**{**cfg.__dict__, "store_cast": None}), W, [7, 12], seed=9)
+        outs[name] = fo.focus_step(cfg, W, pool, states, keep_override=[[0, 2, 5, 6], [1, 2, 3, 7]])
+    np.testing.assert_allclose(outs["identity"].logits, outs["off"].logits, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(outs["identity"].delta_I[0], outs["off"].delta_I[0], rtol=1e-12, atol=1e-12)
+    err = np.max(np.abs(outs["bf16"].logits - outs["off"].logits)) / np.max(np.abs(outs["off"].logits))
+    assert 1e-4 < err < 2e-2, err
+    # the rounding itself: nearest-even to 8 significant bits
+    assert round_bf16(np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, -3.14159, 1e-40])).tolist()[:2] == [1.0, 1.0 + 2.0 ** -6]
