@@ -254,6 +254,15 @@ int focus_finalize_blocks(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const
 int focus_run_steps(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32_t *seq_slot, int32_t n_steps, int32_t finalize,
                     int64_t *decoded, const focus_step_out *out);
 
+/* Launch-shape hint for steps whose packed row count only the device knows (Eq. 4-5 dynamic budget, the structural constraints
+ * of Sec. 4.2, the intra-block cache of Sec. 4.3, per-sequence budgets): without it every launch of the reduced forward pass is
+ * shaped for the worst case n_seq * B.  packed_rows = rows the next steps are expected to retain in total (e.g. the last step's
+ * cu_seqlens[n_seq]), rows_per_seq = the most a single sequence is expected to retain; 0 = no hint.  Only tile shapes, K splits
+ * and wavefront counts follow the hint: results do not depend on it in any way other than the rounding order of K-split
+ * projections, and a step that retains more rows than hinted is still computed in full (more workgroups per projection, several
+ * passes of the attention over that sequence's K/V).  Applies to every later focus_step / focus_run_steps of the context. */
+int focus_set_row_hint(focus_ctx *ctx, int32_t packed_rows, int32_t rows_per_seq);
+
 /* Teacher forcing for mixture-of-experts layers: from now on focus_step and focus_run_layers use, for the row of block
  * position p of batch entry b in layer l, the experts experts[(l * max_batch * B + b * B + p) * k + j], j < k (distinct,
  * in 0..E-1; out-of-range values are clamped), with weights computed from the router logits as for the router's own pick.
@@ -278,13 +287,16 @@ int focus_set_state(focus_ctx *ctx, int32_t slot, const focus_seq_state *state);
  * duration and the number of launches of one class. */
 enum { FOCUS_KC_GEMM = 0,      /* dense projections: QKV, O, gate/up, down, lm_head */
        FOCUS_KC_ATTENTION = 1, /* block attention over the paged K/V */
-       FOCUS_KC_EVICT = 2,     /* importance, budget + selection, scan, gather */
-       FOCUS_KC_POINTWISE = 3, /* embedding, RMSNorm, rotary + K/V write, SiLU*up */
+       FOCUS_KC_IMPORTANCE = 2,/* token importance of layers e-1 and e (Eq. 2) */
+       FOCUS_KC_POINTWISE = 3, /* embedding, RMSNorm, SiLU*up, row bookkeeping */
        FOCUS_KC_DECODE = 4,    /* confidence over the vocabulary, commit */
        FOCUS_KC_ROUTE = 5,     /* mixture-of-experts: picks, sorting by expert, weighted sum */
        FOCUS_KC_EXPERTS = 6,   /* mixture-of-experts: the grouped gate/up and down projections of the routed experts
                                   (router and shared expert are dense projections, FOCUS_KC_GEMM) */
-       FOCUS_KC_COUNT = 7 };
+       FOCUS_KC_SELECT = 7,    /* delta, budget, selection (Eq. 3-5, Alg. 1 phase 3) and the prefix-sum packing */
+       FOCUS_KC_GATHER = 8,    /* gather of the retained rows into the packed batch */
+       FOCUS_KC_KV_WRITE = 9,  /* rotary embedding + scatter of K and V into the paged cache */
+       FOCUS_KC_COUNT = 10 };
 int focus_set_timing(focus_ctx *ctx, int32_t enable);
 int focus_get_kernel_time(focus_ctx *ctx, int32_t kernel_class, float *total_ms, int32_t *launches);
 

@@ -18,8 +18,8 @@ LIB_PATH = os.path.join(_HERE, "libfocus.so")
 FOCUS_OK, FOCUS_EINVAL, FOCUS_ENOMEM, FOCUS_EHIP = 0, -1, -2, -3
 FOCUS_F32, FOCUS_BF16 = 0, 1
 FOCUS_MAX_BLOCK = 64
-KC_GEMM, KC_ATTENTION, KC_EVICT, KC_POINTWISE, KC_DECODE, KC_ROUTE, KC_EXPERTS, KC_COUNT = 0, 1, 2, 3, 4, 5, 6, 7
-KC_NAMES = ["gemm", "attention", "evict", "pointwise", "decode", "route", "experts"]
+KC_GEMM, KC_ATTENTION, KC_IMPORTANCE, KC_POINTWISE, KC_DECODE, KC_ROUTE, KC_EXPERTS, KC_SELECT, KC_GATHER, KC_KV_WRITE, KC_COUNT = range(11)
+KC_NAMES = ["gemm", "attention", "importance", "pointwise", "decode", "route", "experts", "select", "gather", "kv_write"]
 
 
 class focus_config(C.Structure):
@@ -81,6 +81,7 @@ def load_library() -> C.CDLL:
         "focus_run_layers": [P, P, I, P, P, P, I, I, P],
         "focus_finalize_blocks": [P, P, I, P, P],
         "focus_set_route_override": [P, P],
+        "focus_set_row_hint": [P, I, I],
         "focus_run_steps": [P, P, I, P, I, I, P, C.POINTER(focus_step_out)],
         "focus_get_state": [P, I, C.POINTER(focus_seq_state)],
         "focus_set_state": [P, I, C.POINTER(focus_seq_state)],
@@ -97,7 +98,7 @@ def load_library() -> C.CDLL:
 
 _lib = load_library()
 EXPORTS = ["focus_workspace_bytes", "focus_kv_pool_bytes", "focus_init", "focus_prefill_kv", "focus_step",
-           "focus_select_compact", "focus_select_compact_noalloc", "focus_commit", "focus_run_layers", "focus_finalize_blocks", "focus_set_route_override", "focus_run_steps", "focus_get_state", "focus_set_state", "focus_set_timing",
+           "focus_select_compact", "focus_select_compact_noalloc", "focus_commit", "focus_run_layers", "focus_finalize_blocks", "focus_set_route_override", "focus_set_row_hint", "focus_run_steps", "focus_get_state", "focus_set_state", "focus_set_timing",
            "focus_get_kernel_time", "focus_free", "focus_last_error"]
 
 
@@ -218,6 +219,9 @@ class Focus:
     def focus_set_route_override(self, experts: Optional[torch.Tensor]):
         self._route_override = experts       # borrowed by the library
         _check(_lib.focus_set_route_override(self._ctx, _ptr(experts)), self._ctx)
+
+    def focus_set_row_hint(self, packed_rows: int, rows_per_seq: int = 0):
+        _check(_lib.focus_set_row_hint(self._ctx, packed_rows, rows_per_seq), self._ctx)
 
     def focus_get_state(self, slot: int) -> focus_seq_state:
         st = focus_seq_state()

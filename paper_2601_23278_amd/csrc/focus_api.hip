@@ -175,6 +175,7 @@ struct focus_ctx {
   int n_timed = 0;
   hipStream_t last_stream = nullptr;
   int max_total = 0;                   // host-side bound of prefix_len + B over the installed sequences
+  int hint_rows = 0, hint_rows_per_seq = 0;   // focus_set_row_hint: expected packed rows of a step / per sequence (0: none)
 
   template <typename T> T *at(size_t off) const { return (T *)(ws + off); }
   fk::SlotState slots() const {
@@ -278,7 +279,7 @@ void layer_qkv(focus_ctx *c, hipStream_t s, int l, const RowSet &rs, const float
   void *normed = c->at<char>(c->plan.off_normed), *qkv = c->at<char>(c->plan.off_qkv);
   { Timed t(c, s, FOCUS_KC_POINTWISE); fk::rmsnorm(s, g.dtype, resid, c->attn_norm[l], normed, g.hidden, g.rms_eps, rs.rows); }
   { Timed t(c, s, FOCUS_KC_GEMM); fk::gemm(s, g.dtype, normed, c->w_qkv[l], qkv_w, g.hidden, rs.rows, fk::EPI_STORE, qkv, qkv_w, fk::Warm(), c->scratch()); }
-  { Timed t(c, s, FOCUS_KC_POINTWISE);
+  { Timed t(c, s, FOCUS_KC_KV_WRITE);
     fk::rope_kv_write(s, g.dtype, qkv, g.n_q_heads, rs.rows, rs.ri, c->slots(), c->kv_layer(l), c->at<float2>(c->plan.off_rope), rs.n_seq, rs.cu); }
 }
 
@@ -692,7 +693,7 @@ int focus_step(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32_t *s
   for (int l = 0; l < e; ++l) {
     layer_qkv(ctx, s, l, full, resid);
     if (l == e - 1 && g.importance_mode == 0) {
-      Timed t(ctx, s, FOCUS_KC_EVICT);
+      Timed t(ctx, s, FOCUS_KC_IMPORTANCE);
       fk::importance(s, g.dtype, qkv, cu_full, n_seq, B, g.n_q_heads, g.n_kv_heads, g.head_dim, g.maxpool_k, seq_slot, st, ctx->kv_layer(l), partial);
     }
     layer_rest(ctx, s, l, full, resid, qkv, qkv_w, nullptr);
@@ -702,10 +703,11 @@ int focus_step(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32_t *s
   layer_qkv(ctx, s, e, full, resid);
 
   // phase 2 + 3a: delta, budget, selection, packing, gather
-  {
-    Timed t(ctx, s, FOCUS_KC_EVICT);
+  { Timed t(ctx, s, FOCUS_KC_IMPORTANCE);
     fk::importance(s, g.dtype, qkv, cu_full, n_seq, B, g.n_q_heads, g.n_kv_heads, g.head_dim, g.maxpool_k, seq_slot, st, ctx->kv_layer(e),
-                   partial + partial_stride);
+                   partial + partial_stride); }
+  {
+    Timed t(ctx, s, FOCUS_KC_SELECT);
     fk::SelectArgs a{};
     a.n_seq = n_seq; a.B = B; a.n_q_heads = g.n_q_heads;
     a.partial_prev = partial; a.partial_evict = partial + partial_stride; a.delta_in = nullptr;
@@ -720,9 +722,13 @@ int focus_step(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32_t *s
     fk::select(s, a);
     fk::scan_compact(s, n_seq, B, keep, cu, row_map, total);
   }
+  // the packed row count is read from device memory by every kernel; `cap` bounds it (grids, buffers), the caller's hint,
+  // when there is one, shapes tiles, K splits and the attention's wavefront count
   const int cap = packed_cap(g, n_seq, keep_override != nullptr);
-  RowSet packed{{cap, total}, {row_map, seq_slot, B}, n_seq, cu, n_seq > 0 ? (cap + n_seq - 1) / n_seq : 0, ctx->at<int32_t>(pl.off_order)};
-  { Timed t(ctx, s, FOCUS_KC_EVICT);
+  const int rows_per_seq_cap = n_seq > 0 ? (cap + n_seq - 1) / n_seq : 0;
+  const int rows_per_seq = ctx->hint_rows_per_seq > 0 ? std::min(ctx->hint_rows_per_seq, rows_per_seq_cap) : rows_per_seq_cap;
+  RowSet packed{{cap, total, ctx->hint_rows}, {row_map, seq_slot, B}, n_seq, cu, rows_per_seq, ctx->at<int32_t>(pl.off_order)};
+  { Timed t(ctx, s, FOCUS_KC_GATHER);
     fk::gather_rows(s, g.dtype, packed.rows, row_map, B, cu_full, dc ? uncached : nullptr, resid, resid_p, g.hidden, qkv, qkv_w, q_p, q_w); }
 
   // phase 3b: rest of layer e (all B fresh keys of layer e are visible), then the layers above on packed rows
@@ -889,6 +895,14 @@ int focus_run_steps(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32
       if (int rc = focus_finalize_blocks(ctx, hip_stream, n_seq, seq_slot, nullptr)) return rc;
   }
   HIP_TRY(ctx, hipGetLastError());
+  return FOCUS_OK;
+}
+
+int focus_set_row_hint(focus_ctx *ctx, int32_t packed_rows, int32_t rows_per_seq) {
+  if (!ctx) return fail(nullptr, FOCUS_EINVAL, "null context");
+  if (packed_rows < 0 || rows_per_seq < 0) return fail(ctx, FOCUS_EINVAL, "row hints must be >= 0");
+  ctx->hint_rows = packed_rows;
+  ctx->hint_rows_per_seq = rows_per_seq;
   return FOCUS_OK;
 }
 

@@ -18,6 +18,9 @@ namespace fk {
 struct Rows {
   int cap;
   const int32_t *count;
+  int hint = 0;   // the host's guess of *count (0: none, plan for cap).  Tile shapes and K splits are chosen for it; a wrong
+                  // guess costs time, never correctness: grids are sized for cap and kernels work from *count
+  int expected() const { return hint > 0 && hint < cap ? hint : cap; }
 };
 
 // Device arrays indexed by sequence slot.
@@ -106,7 +109,8 @@ struct AttnArgs {
   int q_stride, n_q_heads;
   int n_seq;
   const int32_t *cu;             // rows of sequence b are cu[b] .. cu[b + 1]
-  int max_rows_per_seq;          // host-known bound of cu[b + 1] - cu[b]
+  int max_rows_per_seq;          // rows per sequence the launch is shaped for (wavefronts per workgroup); a sequence with
+                                 // more rows takes several passes over its K/V
   Rows rows;
   RowIndex ri;
   SlotState st;

@@ -109,21 +109,7 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_mfma(AttnArgs a) {
   const int t1 = split == nsplit - 1 ? total : t0 + a.chunk;
   const uint64_t vis = a.vis_by_b ? a.vis_by_b[b] : ~0ull;
   const int32_t *pt = a.st.page_table + (size_t)slot * a.st.table_stride;
-  const int R = min(nr * g, NW * 32);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5, col = lane & 31;
-  const int qi = wave * 32 + col;
-  const bool wave_has_rows = wave * 32 < R, qvalid = qi < R;
-  const int qrow = r0 + (qvalid ? qi / g : 0), qhead = hk * g + (qvalid ? qi % g : 0);
-
-  bf16x8 qf[8];
-  {
-    const bf16_t *qp = (const bf16_t *)a.q + (size_t)qrow * a.q_stride + (size_t)qhead * D + 8 * half;
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      u32x4 v = qvalid ? *(const u32x4 *)(qp + 16 * ks) : (u32x4){0, 0, 0, 0};
-      qf[ks] = __builtin_bit_cast(bf16x8, v);
-    }
-  }
 
   // Tiles go from global memory straight into LDS (global_load_lds_dwordx4: lane l of an instruction fills
   // the 16-byte slot l of a 1 KB LDS block), so the swizzle is applied on the global side: the lane that owns
@@ -162,13 +148,35 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_mfma(AttnArgs a) {
       __builtin_amdgcn_global_load_lds(FK_GLB_PTR(pg + gv[q]), FK_LDS_PTR(Vs + (wave * IPW + q) * 1024), 16, 0, 0);
   };
 
+  const float sc = 1.4426950408889634f / sqrtf((float)D);      // scores in the log2 domain
+  // The workgroup holds NW * 32 (row, group head) pairs at a time.  The launch is sized for the rows a sequence is expected
+  // to have; a sequence with more takes further passes over its K/V range (correct for any row count, one stream per pass).
+  const int RT = nr * g;
+  for (int q0 = 0; q0 < RT; q0 += NW * 32) {
+  const int R = min(RT - q0, NW * 32);
+  const int qi = q0 + wave * 32 + col;
+  const bool wave_has_rows = wave * 32 < R, qvalid = wave * 32 + col < R;
+  const int qrow = r0 + (qvalid ? qi / g : 0), qhead = hk * g + (qvalid ? qi % g : 0);
+  bf16x8 qf[8];
+  {
+    const bf16_t *qp = (const bf16_t *)a.q + (size_t)qrow * a.q_stride + (size_t)qhead * D + 8 * half;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      u32x4 v = qvalid ? *(const u32x4 *)(qp + 16 * ks) : (u32x4){0, 0, 0, 0};
+      qf[ks] = __builtin_bit_cast(bf16x8, v);
+    }
+  }
+  if (q0 > 0) {                                                // a further pass starts from the first tile again
+    ptreg = pt[min(tile0 + lane, tile1 - 1)];
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    __builtin_amdgcn_s_barrier();
+  }
   f32x16 oacc[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int r = 0; r < 16; ++r) oacc[i][r] = 0.f;
   float m = -INFINITY, l = 0.f;
-  const float sc = 1.4426950408889634f / sqrtf((float)D);      // scores in the log2 domain
 
   // One K buffer and one V^T buffer, refilled as soon as the product that reads them is done: the K tile of
   // the next step streams in during this step's softmax and P V product, the V tile during the next step's
@@ -259,12 +267,8 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_mfma(AttnArgs a) {
     if (more) issue_v(tile + 1);
   }
 
-  // the last workgroups to start (the shortest sequences), once through their own K/V, pull the next projection's
-  // weights into the memory-side cache: any earlier and the K/V stream would push them out again
-  const unsigned warm_acc = warm_touch(a.warm.ptr, a.warm.bytes, NW * 64);
-  if (warm_acc == 0x9e3779b9u && a.chunk < 0) ((unsigned *)a.out)[0] = warm_acc;   // never true: keeps the loads
-  if (!qvalid) return;
   const float l_tot = l + __shfl_xor(l, 32);
+  if (!qvalid) continue;
   if (nsplit == 1) {
     const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
     bf16_t *orow = (bf16_t *)a.out + (size_t)qrow * Hq * D + (size_t)qhead * D;
@@ -292,6 +296,11 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_mfma(AttnArgs a) {
       a.part_ml[pi * 2 + 1] = l_tot;
     }
   }
+  }   // passes
+  // the last workgroups to start (the shortest sequences), once through their own K/V, pull the next projection's
+  // weights into the memory-side cache: any earlier and the K/V stream would push them out again
+  const unsigned warm_acc = warm_touch(a.warm.ptr, a.warm.bytes, NW * 64);
+  if (warm_acc == 0x9e3779b9u && a.chunk < 0) ((unsigned *)a.out)[0] = warm_acc;   // never true: keeps the loads
 }
 
 // Merge of the K/V splits of one (row, head): out = sum_s o_s 2^(m_s - M) / sum_s l_s 2^(m_s - M), in split order.
@@ -320,8 +329,7 @@ __global__ __launch_bounds__(128) void k_attn_combine(AttnArgs a) {
 void attention(hipStream_t s, const AttnArgs &a) {
   if (a.rows.cap <= 0 || a.n_seq <= 0) return;
   const int g = a.n_q_heads / a.kv.n_kv_heads;
-  const bool mfma = a.dtype == FOCUS_BF16 && a.kv.head_dim == 128 && a.kv.page_size == 64 && a.max_rows_per_seq * g <= 256 &&
-                    a.q_stride % 8 == 0 && a.part_o != nullptr;
+  const bool mfma = a.dtype == FOCUS_BF16 && a.kv.head_dim == 128 && a.kv.page_size == 64 && a.q_stride % 8 == 0 && a.part_o != nullptr;
   if (mfma) {
     dim3 grid(a.n_seq * a.kv.n_kv_heads, a.launch_splits);
     const int R = a.max_rows_per_seq * g;

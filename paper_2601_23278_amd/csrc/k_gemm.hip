@@ -99,7 +99,9 @@ __global__ __launch_bounds__(256, 2) void k_gemm_mfma(const bf16_t *__restrict__
   __shared__ __attribute__((aligned(16))) unsigned char Bs[BN * 128];
 
   const int M = rows.count ? min(*rows.count, rows.cap) : rows.cap;
-  // XCD-aware tile order
+  // XCD-aware tile order over the tile rows that hold valid rows (the grid is sized for rows.cap; with a row count that
+  // only the device knows, the live tiles still spread over all 8 XCDs and the workgroups beyond them exit)
+  tiles_m = min(tiles_m, (M + BM - 1) / BM);
   const int total = tiles_m * tiles_n;
   const int per_xcd = (total + 7) / 8;
   const int tile = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
@@ -270,10 +272,14 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void k_gemm_pipe(const bf
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds_pipe[];
   unsigned char *const lds = lds_pipe;
   const int M = rows.count ? min(*rows.count, rows.cap) : rows.cap;
+  // the tile list covers the tile rows that hold valid rows: the grid is sized for rows.cap, and with a row count that only the
+  // device knows the live tiles still spread evenly over the 8 XCDs (workgroups beyond them exit at once)
+  tiles_m = min(tiles_m, (M + BM - 1) / BM);
   const int total = tiles_m * tiles_n * splits;
   const int per_xcd = (total + 7) / 8;
   const int work = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
   if (blockIdx.x / 8 >= per_xcd || work >= total) return;
+  const int live_grid = per_xcd * 8;
   const int tile = work / splits, split = work % splits;
   constexpr int GROUP = 8;
   const int in_group = tile % (GROUP * tiles_n), first_m = (tile / (GROUP * tiles_n)) * GROUP;
@@ -312,7 +318,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void k_gemm_pipe(const bf
   __amdgpu_buffer_rsrc_t rs_p = __builtin_amdgcn_make_buffer_rsrc((void *)warm, 0, warm_bytes, 0x00020000);
   // only the workgroups of the last round (one workgroup per CU) take part: what earlier rounds fetch is pushed out of the
   // cache again by the kernel's own traffic before the next kernel starts
-  const int warm_groups = min((int)gridDim.x, 256), warm_rank = (int)blockIdx.x - ((int)gridDim.x - warm_groups);
+  const int warm_groups = min(live_grid, 256), warm_rank = (int)blockIdx.x - (live_grid - warm_groups);
   constexpr unsigned HIT = NW * 8192;   // bytes per hit: NW wavefronts x 64 lines
   const unsigned warm_hits = warm_rank < 0 ? 0u : ((warm_bytes + warm_groups - 1) / warm_groups + HIT - 1) / HIT;
   const int warm_stride = warm_hits ? max(1, nk / (int)warm_hits) : 1;
@@ -561,13 +567,15 @@ void gemm(hipStream_t s, int dtype, const void *A, const void *W, int N, int K, 
   // (byte offsets of rows must fit 32 bits there, and the slab count must be even), else the register-staged kernel with smaller tiles
   const long n_tiles = epilogue == EPI_SILU_MUL ? (N / 2 + 127) / 128 : (N + 255) / 256;
   const bool fits32 = (double)std::max(rows.cap + 256, N + 256) * K * 2 < 4.0e9 && (K / 64) % 2 == 0;
-  const long t256 = (long)((rows.cap + 255) / 256) * n_tiles, t128 = (long)((rows.cap + 127) / 128) * n_tiles;
+  // (tile shapes are chosen for the expected row count; the grids below cover rows.cap)
+  const int est = rows.expected();
+  const long t256 = (long)((est + 255) / 256) * n_tiles, t128 = (long)((est + 127) / 128) * n_tiles;
   const int choice = t256 >= 160 ? 256 : (t128 >= 160 ? 128 : 0);
   // four wavefronts of 128 x 128 read a third less from LDS per MFMA: measured 2-5 % faster where the launch takes more
   // than one round of workgroups (gate/up, vocabulary projection, full-block layers), no gain on single-round launches
   const bool four = t256 > 256;
   // one round of 256-wide tiles that leaves CUs idle (the QKV projection of 2048 rows: 192 tiles): 192-wide tiles fill them
-  const long t192 = N % 192 == 0 ? (long)((rows.cap + 255) / 256) * (N / 192) : 0;
+  const long t192 = N % 192 == 0 ? (long)((est + 255) / 256) * (N / 192) : 0;
   if (fits32 && choice == 256 && !four && t256 < 240 && t192 > t256 && t192 <= 256 && epilogue != EPI_SILU_MUL) {
     const int tm = (rows.cap + 255) / 256, tn = N / 192;
     const bf16_t *a = (const bf16_t *)A, *w = (const bf16_t *)W;
@@ -602,7 +610,7 @@ void gemm(hipStream_t s, int dtype, const void *A, const void *W, int N, int K, 
     if (splits > 1 && launch_split(s, A, W, N, K, rows, epilogue, out, ldo, warm, splits, (float *)scratch.ptr)) return;
     if (launch_pipe<128, 8>(s, A, W, N, K, rows, epilogue, out, ldo, warm)) return;
   }
-  const long tiles_big = (long)((rows.cap + 255) / 256) * ((N + 127) / 128);
+  const long tiles_big = (long)((est + 255) / 256) * ((N + 127) / 128);
   if (tiles_big >= 512) launch_mfma<256, 128>(s, A, W, N, K, rows, epilogue, out, ldo);
   else launch_mfma<128, 128>(s, A, W, N, K, rows, epilogue, out, ldo);
 }

@@ -252,10 +252,28 @@ __global__ __launch_bounds__(256) void k_gather(Rows rows, const int32_t *row_ma
   }
   const float4 *a = (const float4 *)(resid + (size_t)src * hidden);
   float4 *o = (float4 *)(resid_p + (size_t)r * hidden);
-  for (int i = threadIdx.x; i < hidden / 4; i += 256) o[i] = a[i];
   const T *q = qkv + (size_t)src * qkv_stride;
   T *qo = q_p + (size_t)r * q_width;
-  for (int i = threadIdx.x; i < q_width; i += 256) qo[i] = q[i];
+  constexpr int QV = 16 / sizeof(T);                       // query elements per 16-byte piece
+  const bool qvec = q_width % QV == 0 && qkv_stride % QV == 0 && (((size_t)qkv | (size_t)q_p) & 15) == 0;
+  const int n4 = hidden / 4, nq = qvec ? q_width / QV : 0;
+  if (n4 <= 1024 && nq <= 512) {
+    // the usual row (hidden <= 4096, H_q D <= 4096 bf16): every load of the row is in flight before the first store
+    float4 v[4], w[2];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) if ((int)threadIdx.x + 256 * k < n4) v[k] = a[threadIdx.x + 256 * k];
+#pragma unroll
+    for (int k = 0; k < 2; ++k) if ((int)threadIdx.x + 256 * k < nq) w[k] = ((const float4 *)q)[threadIdx.x + 256 * k];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) if ((int)threadIdx.x + 256 * k < n4) o[threadIdx.x + 256 * k] = v[k];
+#pragma unroll
+    for (int k = 0; k < 2; ++k) if ((int)threadIdx.x + 256 * k < nq) ((float4 *)qo)[threadIdx.x + 256 * k] = w[k];
+  } else {
+    for (int i = threadIdx.x; i < n4; i += 256) o[i] = a[i];
+    for (int i = threadIdx.x; i < nq; i += 256) ((float4 *)qo)[i] = ((const float4 *)q)[i];
+  }
+  if (!qvec)
+    for (int i = threadIdx.x; i < q_width; i += 256) qo[i] = q[i];
 }
 
 void gather_rows(hipStream_t s, int dtype, Rows rows, const int32_t *row_map, int B, const int32_t *src_cu, const uint64_t *src_bits,

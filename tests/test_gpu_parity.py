@@ -107,10 +107,12 @@ def check_routes(wl, g, tr, tol, exact):
         assert np.all(g["route_experts"][l, idle] == -1), l
 
 
-def compare_steps(wl, steps, tol, exact, seq_ids=None, k_override=None, forced_routes=False):
+def compare_steps(wl, steps, tol, exact, seq_ids=None, k_override=None, forced_routes=False, row_hint=None):
     pk, runner = _pk()
     cfg, W, pool, states, lens, tables, n_pages = oracle_batch(wl, seq_ids)
     sess = runner.open_session(wl, DEV, seq_ids)
+    if row_hint is not None:
+        sess.focus.focus_set_row_hint(*row_hint)
     n, B = len(states), wl.block_size
     outs = Outs(pk, wl, n)
     routes = None
@@ -324,6 +326,20 @@ def small_bf16(**over):
 
 def test_small_bf16_teacher_forced():
     compare_steps(small_bf16(), 3, 2e-2, exact=False)
+
+
+@pytest.mark.parametrize("hint", [(8, 2), (48, 8), (100000, 64)])
+def test_small_bf16_dynamic_budget_and_constraints_with_row_hints(hint):
+    """The method's own operating mode (Eq. 4-5 budget with alpha 1.5, both constraints of Sec. 4.2): the packed row count is
+    known on the device only.  A launch-shape hint that is too small (sequences then take several attention passes and the
+    projections more workgroups than planned), about right, or far too large must not change what is computed."""
+    compare_steps(small_bf16(budget_mode=2, constraints=3, batch=7), 3, 2e-2, exact=False, row_hint=hint)
+
+
+def test_small_bf16_block64_dense_with_a_one_row_hint():
+    """Nothing is evicted (ratio 1.0, 64 rows per sequence and 4 query heads per kv head: 256 (row, head) pairs) while the hint
+    promises one row per sequence: the packed layers' attention runs with one wavefront and eight passes per sequence."""
+    compare_steps(small_bf16(block_size=64, keep_ratio=1.0, batch=3, prefix_lo=100, prefix_hi=300), 2, 2e-2, exact=False, row_hint=(3, 1))
 
 
 def test_small_bf16_intra_block_cache_teacher_forced():
