@@ -83,9 +83,11 @@ def fill_normal_(out: torch.Tensor, seed: int, tensor_id: int, std: float,
     n = flat.numel()
     if chunk is None:
         chunk = (1 << 18) if out.device.type == "cpu" else (1 << 26)
-    for s in range(0, n, chunk):
+    for i, s in enumerate(range(0, n, chunk)):
         c = min(chunk, n - s)
         flat[s:s + c] = normal_values(seed, tensor_id, s, c, std, device=out.device, dtype=out.dtype)
+        if out.device.type != "cpu" and i % 32 == 31:
+            torch.cuda.synchronize(out.device)     # bounds the queue of pending launches (a profiler that counts every dispatch needs that)
     return out
 
 

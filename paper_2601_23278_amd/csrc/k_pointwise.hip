@@ -257,21 +257,10 @@ __global__ __launch_bounds__(256) void k_gather(Rows rows, const int32_t *row_ma
   constexpr int QV = 16 / sizeof(T);                       // query elements per 16-byte piece
   const bool qvec = q_width % QV == 0 && qkv_stride % QV == 0 && (((size_t)qkv | (size_t)q_p) & 15) == 0;
   const int n4 = hidden / 4, nq = qvec ? q_width / QV : 0;
-  if (n4 <= 1024 && nq <= 512) {
-    // the usual row (hidden <= 4096, H_q D <= 4096 bf16): every load of the row is in flight before the first store
-    float4 v[4], w[2];
-#pragma unroll
-    for (int k = 0; k < 4; ++k) if ((int)threadIdx.x + 256 * k < n4) v[k] = a[threadIdx.x + 256 * k];
-#pragma unroll
-    for (int k = 0; k < 2; ++k) if ((int)threadIdx.x + 256 * k < nq) w[k] = ((const float4 *)q)[threadIdx.x + 256 * k];
-#pragma unroll
-    for (int k = 0; k < 4; ++k) if ((int)threadIdx.x + 256 * k < n4) o[threadIdx.x + 256 * k] = v[k];
-#pragma unroll
-    for (int k = 0; k < 2; ++k) if ((int)threadIdx.x + 256 * k < nq) ((float4 *)qo)[threadIdx.x + 256 * k] = w[k];
-  } else {
-    for (int i = threadIdx.x; i < n4; i += 256) o[i] = a[i];
-    for (int i = threadIdx.x; i < nq; i += 256) ((float4 *)qo)[i] = ((const float4 *)q)[i];
-  }
+  // plain load-store pairs: all workgroups of the launch start together, and a kernel that first reads its whole row and then
+  // writes it makes the chip alternate between a read phase and a write phase (measured: 35 us against 23 us for 100 MB)
+  for (int i = threadIdx.x; i < n4; i += 256) o[i] = a[i];
+  for (int i = threadIdx.x; i < nq; i += 256) ((float4 *)qo)[i] = ((const float4 *)q)[i];
   if (!qvec)
     for (int i = threadIdx.x; i < q_width; i += 256) qo[i] = q[i];
 }
