@@ -743,10 +743,20 @@ int focus_step(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32_t *s
   // decode and verify
   void *normed = ctx->at<char>(pl.off_normed);
   { Timed t(ctx, s, FOCUS_KC_POINTWISE); fk::rmsnorm(s, g.dtype, resid_p, ctx->final_norm, normed, g.hidden, g.rms_eps, packed.rows); }
-  { Timed t(ctx, s, FOCUS_KC_GEMM); fk::gemm(s, g.dtype, normed, ctx->lm_head, g.vocab, g.hidden, packed.rows, fk::EPI_STORE_F32, logits, g.vocab, fk::Warm(), ctx->scratch()); }
+  // without a logits output the projection reduces every row to (max, sum exp, arg-max) triples per column range in its epilogue
+  // and the logits never reach memory; the triples take the place of the logits in the workspace
+  int conf_slots = 0;
+  bool fused_conf = false;
+  if (!o.logits) {
+    Timed t(ctx, s, FOCUS_KC_GEMM);
+    fused_conf = fk::gemm_conf_partials(s, g.dtype, normed, ctx->lm_head, g.vocab, g.hidden, packed.rows, ctx->at<float>(pl.off_logits),
+                                        (size_t)ctx->plan.max_rows * g.vocab * 4, &conf_slots);
+  }
+  if (!fused_conf) { Timed t(ctx, s, FOCUS_KC_GEMM); fk::gemm(s, g.dtype, normed, ctx->lm_head, g.vocab, g.hidden, packed.rows, fk::EPI_STORE_F32, logits, g.vocab, fk::Warm(), ctx->scratch()); }
   {
     Timed t(ctx, s, FOCUS_KC_DECODE);
-    fk::confidence(s, logits, g.vocab, packed.rows, conf, amax, ctx->scratch());
+    if (fused_conf) fk::confidence_from_partials(s, ctx->at<float>(pl.off_logits), conf_slots, packed.rows, conf, amax);
+    else fk::confidence(s, logits, g.vocab, packed.rows, conf, amax, ctx->scratch());
     fk::CommitArgs ca{n_seq, B, seq_slot, st, keep, cu, conf, amax, g.conf_threshold, g.mask_token_id, g.intra_block_cache, o.tokens, o.mask_bits, o.n_decoded};
     fk::commit(s, ca);
   }

@@ -65,8 +65,18 @@ enum Epilogue {
   EPI_ADD_F32 = 1,   // out[f32] += acc
   EPI_STORE_F32 = 2, // out[f32] = acc
   EPI_SILU_MUL = 3,  // W = [gate rows; up rows] (N = 2F): out[dtype][m, f] = silu(gate) * up; only where gemm_fuses_silu_mul()
-  EPI_PARTIAL_SILU = 4   // internal to the K-split path: fp32 sums of the gate and up columns, weight-row order
+  EPI_PARTIAL_SILU = 4,  // internal to the K-split path: fp32 sums of the gate and up columns, weight-row order
+  EPI_CONF = 5           // vocabulary projection without logits: per row and column range (max, sum exp(x - max), arg-max); only
+                         // through gemm_conf_partials()
 };
+// Vocabulary projection fused with the first half of the confidence computation (Alg. 1 Decode_and_Verify): every wavefront of a
+// projection tile reduces its columns of a row to (maximum, sum of exp(logit - maximum), lowest index of the maximum) and writes
+// that triple to part[row * n_slots + slot] (3 floats, the index as int bits); confidence_from_partials() merges a row's slots in
+// slot order.  The logits never reach memory.  False when the shape is not taken (few rows, fp32 model): the caller then
+// materialises the logits and runs confidence().
+bool gemm_conf_partials(hipStream_t s, int dtype, const void *A, const void *W, int N, int K, Rows rows, float *part, size_t part_bytes,
+                        int *n_slots);
+void confidence_from_partials(hipStream_t s, const float *part, int n_slots, Rows rows, float *conf, int32_t *argmax);
 bool gemm_fuses_silu_mul(int dtype, const void *A, const void *W, int N, int K);
 
 void embed(hipStream_t s, int dtype, const void *table, int hidden, Rows rows, RowIndex ri, SlotState st,

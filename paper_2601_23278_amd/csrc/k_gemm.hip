@@ -7,7 +7,6 @@
 //   k_gemm_mfma  bf16 on the matrix cores (see below).
 // M is read from device memory when the row count is only known on the device (packed batch after eviction).
 #include <algorithm>
-#include <cstdlib>
 
 #include "focus_internal.h"
 
@@ -252,7 +251,7 @@ __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-template <int BM, int NW, int EPI, int BN = 256, int KS = 1>
+template <int BM, int NW, int EPI, int BN = 256>
 __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void k_gemm_pipe(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W, int N, int K,
                                                       Rows rows, void *out, int ldo, int tiles_m, int tiles_n, const void *warm,
                                                       unsigned warm_bytes, int splits, size_t split_stride) {
@@ -263,14 +262,8 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void k_gemm_pipe(const bf
   // NW = 8: wavefronts 2 x 4, each BM/2 x 64;  NW = 4: wavefronts 2 x 2, each BM/2 x 128 (a third fewer LDS reads per MFMA,
   // accumulators in the 256 accumulation registers a lone wavefront per SIMD can have)
   // BN = 192 (4 wavefronts of 128 x 96) exists for launches whose 256-wide tiles would leave a quarter of the CUs idle
-  // KS = 2 (NW = 4): the four wavefronts are 2 (k halves) x 2 (column halves); a wavefront owns a BM x BN/2 patch for the two
-  // k-steps of every slab that belong to its half, so that with BM = 128 its tile is 128 x 128 (one LDS fragment read per two
-  // MFMAs instead of one per MFMA for the 64 x 64 patches of the 8-wavefront layout) although the workgroup's tile is only
-  // 128 x 256.  The two partial sums of a patch are added through LDS at the end, always as (first k half) + (second k half).
-  constexpr int BK = 64, WCOLS = KS == 2 ? 2 : NW / 2, WM = KS == 2 ? BM : BM / 2, WN = BN / WCOLS, TM = WM / 32, TN = WN / 32;
-  constexpr int NKS = 4 / KS;        // k-steps of a slab that one wavefront multiplies
+  constexpr int BK = 64, WCOLS = NW / 2, WM = BM / 2, WN = BN / WCOLS, TM = WM / 32, TN = WN / 32;
   static_assert(WN % 32 == 0 && (BN / 8) % NW == 0 && (!SILU_W || TN % 2 == 0), "tile shape");
-  static_assert(KS == 1 || (KS == 2 && NW == 4 && TM % 2 == 0 && (EPI == EPI_ADD_F32 || EPI == EPI_STORE || EPI == EPI_STORE_F32)), "k-split layout");
   constexpr int IA = BM / 8 / NW, IB = BN / 8 / NW, NI = IA + IB;
   constexpr int ASTAGE = BM * 128, WSTAGE = BN * 128, WBASE = 2 * ASTAGE, NMF = TM * TN;
   // loads issued in the k-step right behind the barrier; the rest follow in the first k-step of the next slab
@@ -297,8 +290,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void k_gemm_pipe(const bf
   const int nk = K / BK / splits;                                 // slabs of this workgroup; even (checked by the host)
   const unsigned k_base = (unsigned)split * (unsigned)nk * (BK * 2);
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int kh = KS == 2 ? wave / 2 : 0;                          // which k half of every slab this wavefront multiplies
-  const int wm = KS == 2 ? 0 : (wave / WCOLS) * WM, wn = (wave % WCOLS) * WN;
+  const int wm = (wave / WCOLS) * WM, wn = (wave % WCOLS) * WN;
   // raw buffers over the valid rows: an offset at or beyond the size reads zero without touching memory
   __amdgpu_buffer_rsrc_t rs_a = __builtin_amdgcn_make_buffer_rsrc((void *)A, 0, (unsigned)M * (unsigned)K * 2u, 0x00020000);
   __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc((void *)W, 0, (unsigned)N * (unsigned)K * 2u, 0x00020000);
@@ -351,12 +343,11 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void k_gemm_pipe(const bf
   // fragment addresses: row = base + (lane & 31), logical chunk 2 * ks + (lane >> 5), swizzled with the row (all 32-row
   // tiles start at a multiple of 32, so the swizzle depends on the lane only)
   const int frow = lane & 31, fch = lane >> 5, sw = (frow >> 1) & 7;
-  const unsigned char *pa[NKS], *pb[NKS];                         // entry q: k-step NKS * kh + q of a slab
+  const unsigned char *pa[4], *pb[4];
 #pragma unroll
-  for (int q = 0; q < NKS; ++q) {
-    const int ks = NKS * kh + q;
-    pa[q] = lds + (wm + frow) * 128 + (((2 * ks + fch) ^ sw) << 4);
-    pb[q] = lds + WBASE + (wn + frow) * 128 + (((2 * ks + fch) ^ sw) << 4);
+  for (int ks = 0; ks < 4; ++ks) {
+    pa[ks] = lds + (wm + frow) * 128 + (((2 * ks + fch) ^ sw) << 4);
+    pb[ks] = lds + WBASE + (wn + frow) * 128 + (((2 * ks + fch) ^ sw) << 4);
   }
   bf16x8 fa[2][TM], fb[2][TN];
   auto rd = [&](int s, int ks, int buf, int slot) {   // s-th fragment read of a k-step, in the order the MFMAs need them
@@ -406,94 +397,26 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void k_gemm_pipe(const bf
     lds_barrier();                     /* ... and everyone's; everyone has read all of this slab */    \
     FK_STEP(1, 0, (buf) ^ 1, L0, 0, so2, buf)                                                           \
   }
-  // the same with two k-steps per wavefront and slab (KS = 2)
-#define FK_SLAB2(buf, kt)                                                                               \
-  {                                                                                                     \
-    const int so1 = min(((kt) + 1) * (BK * 2), last), so2 = min(((kt) + 2) * (BK * 2), last);           \
-    FK_STEP(0, 1, buf, L1, L0, so1, (buf) ^ 1)                                                          \
-    {                                                                                                   \
-      const bool hit = (kt) == warm_next && warm_left > 0;                                              \
-      const unsigned so = hit ? warm_off : 0x80000000u;                                                 \
-      warm_sink ^= warm_prev;                                                                           \
-      warm_prev = __builtin_amdgcn_raw_buffer_load_b32(rs_p, warm_lane, so, 0);                         \
-      warm_off += hit ? HIT : 0u; warm_left -= hit ? 1u : 0u; warm_next += hit ? warm_stride : 0;       \
-    }                                                                                                   \
-    __builtin_amdgcn_s_waitcnt(0x0F71);                                                                 \
-    lds_barrier();                                                                                      \
-    FK_STEP(1, 0, (buf) ^ 1, L0, 0, so2, buf)                                                           \
+  for (int kt = 0; kt < nk; kt += 2) {
+    FK_SLAB(0, kt)
+    FK_SLAB(1, kt + 1)
   }
-  if constexpr (KS == 2) {
-    for (int kt = 0; kt < nk; kt += 2) {
-      FK_SLAB2(0, kt)
-      FK_SLAB2(1, kt + 1)
-    }
-  } else {
-    for (int kt = 0; kt < nk; kt += 2) {
-      FK_SLAB(0, kt)
-      FK_SLAB(1, kt + 1)
-    }
-  }
-#undef FK_SLAB2
 #undef FK_SLAB
 #undef FK_STEP
   __builtin_amdgcn_s_waitcnt(0x0F70);
-  constexpr int TME = KS == 2 ? TM / 2 : TM;      // row tiles a wavefront finishes and stores
-  if constexpr (KS == 2) {
-    // add the two k halves of every patch: the wavefront of the second half hands over its upper TM / 2 row tiles and takes the
-    // lower ones of its partner, through LDS in two rounds of 64 KB (the operand stages are free: every load has landed)
-    lds_barrier();
-    float4 *xch = (float4 *)lds + (size_t)(wave & 1) * (TME * TN * 4 * 64);
-#pragma unroll
-    for (int round = 0; round < 2; ++round) {
-      const int giver = round == 0 ? 1 : 0;       // round 0: row tiles 0 .. TME-1 go from half 1 to half 0; round 1: the rest back
-      if (kh == giver) {
-#pragma unroll
-        for (int i = 0; i < TME; ++i)
-#pragma unroll
-          for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r4 = 0; r4 < 4; ++r4) {
-              const f32x16 &a = acc[round * TME + i][j];
-              xch[((i * TN + j) * 4 + r4) * 64 + lane] = make_float4(a[4 * r4], a[4 * r4 + 1], a[4 * r4 + 2], a[4 * r4 + 3]);
-            }
-      }
-      lds_barrier();
-      if (kh != giver) {
-#pragma unroll
-        for (int i = 0; i < TME; ++i)
-#pragma unroll
-          for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r4 = 0; r4 < 4; ++r4) {
-              const float4 v = xch[((i * TN + j) * 4 + r4) * 64 + lane];
-              f32x16 &a = acc[round * TME + i][j];
-              // (first k half) + (second k half) in both rounds
-              if (round == 0) { a[4 * r4] += v.x; a[4 * r4 + 1] += v.y; a[4 * r4 + 2] += v.z; a[4 * r4 + 3] += v.w; }
-              else { a[4 * r4] = v.x + a[4 * r4]; a[4 * r4 + 1] = v.y + a[4 * r4 + 1]; a[4 * r4 + 2] = v.z + a[4 * r4 + 2]; a[4 * r4 + 3] = v.w + a[4 * r4 + 3]; }
-            }
-      }
-      lds_barrier();
-    }
-    if (kh == 1) {                                // the second half finishes the upper row tiles: move them to the front
-#pragma unroll
-      for (int i = 0; i < TME; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) acc[i][j] = acc[TME + i][j];
-    }
-  }
   if ((warm_sink ^ warm_prev) == 0x9e3779b9u && warm_bytes == 1) ((unsigned *)out)[0] = warm_sink;   // keeps the warm-up loads alive; never true
   // epilogue: accumulator register r of lane l is C[8 * (r / 4) + 4 * (l / 32) + r % 4][l % 32] of its 32x32 tile.
   // A tile that lies inside the matrix takes the path without per-element bounds checks; there the accumulating
   // epilogue reads a whole row of 32x32 tiles before it adds and stores (one memory round trip per tile row instead
   // of one per element).
   const bool inside = m0 + BM <= M && n0 + (SILU_W ? BN / 2 : BN) <= (SILU_W ? N / 2 : N);
-  const int erow = m0 + (KS == 2 ? kh * (TME * 32) : wm) + 4 * (lane >> 5), ecol = lane & 31;
+  const int erow = m0 + wm + 4 * (lane >> 5), ecol = lane & 31;
   if (EPI == EPI_SILU_MUL) {
 #pragma unroll
     for (int jp = 0; jp < TN / 2; ++jp) {
       const int gn = n0 + (wn / 64 + jp) * 32 + ecol;
 #pragma unroll
-      for (int i = 0; i < TME; ++i)
+      for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int gm = erow + i * 32 + 8 * (r >> 2) + (r & 3);
@@ -508,7 +431,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void k_gemm_pipe(const bf
     for (int jp = 0; jp < TN / 2; ++jp) {
       const int gn = n0 + (wn / 64 + jp) * 32 + ecol;
 #pragma unroll
-      for (int i = 0; i < TME; ++i)
+      for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int gm = erow + i * 32 + 8 * (r >> 2) + (r & 3);
@@ -520,10 +443,49 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void k_gemm_pipe(const bf
     }
     return;
   }
+  if (EPI == EPI_CONF) {
+    // per row: (maximum, sum exp(x - maximum), lowest column of the maximum) over this wavefront's WN columns.  A lane holds the
+    // TN values of one row that sit in column ecol of the TN column tiles; the 32 lanes of a lane half hold the same rows.
+    const int slot = (n0 / BN) * WCOLS + wn / WN;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float m = -INFINITY, sum = 0.f;
+        int mi = 0x7fffffff;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const int gn = n0 + wn + j * 32 + ecol;
+          const float v = acc[i][j][r];
+          if (gn < N && v > m) { m = v; mi = gn; }          // ascending columns: the first maximum stays
+        }
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const int gn = n0 + wn + j * 32 + ecol;
+          sum += gn < N ? __expf(acc[i][j][r] - m) : 0.f;
+        }
+#pragma unroll
+        for (int o = 16; o > 0; o >>= 1) {
+          const float om = __shfl_xor(m, o), os = __shfl_xor(sum, o);
+          const int oi = __shfl_xor(mi, o);
+          const float big = fmaxf(m, om);
+          const float fa = m == big ? 1.0f : __expf(m - big), fb = om == big ? 1.0f : __expf(om - big);
+          sum = sum * fa + os * fb;
+          if (om > m || (om == m && oi < mi)) mi = oi;
+          m = big;
+        }
+        const int gm = erow + i * 32 + 8 * (r >> 2) + (r & 3);
+        if (ecol == 0 && gm < M) {
+          float *p = (float *)out + ((size_t)gm * ldo + slot) * 3;
+          p[0] = m; p[1] = sum; p[2] = __int_as_float(mi);
+        }
+      }
+    return;
+  }
   if (EPI == EPI_ADD_F32 && inside) {
     float *o = (float *)out + (size_t)erow * ldo + n0 + wn + ecol;
 #pragma unroll
-    for (int i = 0; i < TME; ++i) {
+    for (int i = 0; i < TM; ++i) {
       float old[TN][16];
 #pragma unroll
       for (int j = 0; j < TN; ++j)
@@ -537,7 +499,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void k_gemm_pipe(const bf
     return;
   }
 #pragma unroll
-  for (int i = 0; i < TME; ++i)
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       const int gn = n0 + wn + j * 32 + ecol;
@@ -578,18 +540,17 @@ __global__ __launch_bounds__(256) void k_splitk_reduce(const float *__restrict__
   }
 }
 
-template <int BM, int NW, int EPI, int BN = 256, int KS = 1>
+template <int BM, int NW, int EPI, int BN = 256>
 static bool launch_pipe_epi(hipStream_t s, const bf16_t *a, const bf16_t *w, int N, int K, Rows rows, void *out, int ldo, int tiles_m, int tiles_n, Warm warm,
                             int splits = 1, size_t split_stride = 0) {
   constexpr int kLds = 2 * (BM + BN) * 128;
-  static_assert(KS == 1 || kLds >= 65536, "the k halves are added through 64 KB of LDS");
   static bool ready = false;             // the dynamic LDS size has to be allowed once per kernel
   if (!ready) {
-    if (hipFuncSetAttribute((const void *)k_gemm_pipe<BM, NW, EPI, BN, KS>, hipFuncAttributeMaxDynamicSharedMemorySize, kLds) != hipSuccess) return false;
+    if (hipFuncSetAttribute((const void *)k_gemm_pipe<BM, NW, EPI, BN>, hipFuncAttributeMaxDynamicSharedMemorySize, kLds) != hipSuccess) return false;
     ready = true;
   }
   const int grid = ((tiles_m * tiles_n * splits + 7) / 8) * 8;
-  k_gemm_pipe<BM, NW, EPI, BN, KS><<<grid, NW * 64, kLds, s>>>(a, w, N, K, rows, out, ldo, tiles_m, tiles_n, warm.ptr, (unsigned)std::min<size_t>(warm.bytes, 0x7fffffffu),
+  k_gemm_pipe<BM, NW, EPI, BN><<<grid, NW * 64, kLds, s>>>(a, w, N, K, rows, out, ldo, tiles_m, tiles_n, warm.ptr, (unsigned)std::min<size_t>(warm.bytes, 0x7fffffffu),
                                                       splits, split_stride);
   return true;
 }
@@ -631,6 +592,31 @@ static bool launch_pipe(hipStream_t s, const void *A, const void *W, int N, int 
   return launch_pipe_epi<BM, NW, EPI_STORE_F32>(s, a, w, N, K, rows, out, ldo, tiles_m, tiles_n, warm);
 }
 
+bool gemm_conf_partials(hipStream_t s, int dtype, const void *A, const void *W, int N, int K, Rows rows, float *part, size_t part_bytes,
+                        int *n_slots) {
+  if (rows.cap <= 0 || dtype != FOCUS_BF16 || K % 64 || (((uintptr_t)A | (uintptr_t)W) & 15)) return false;
+  if (!((double)std::max(rows.cap + 256, N + 256) * K * 2 < 4.0e9 && (K / 64) % 2 == 0)) return false;
+  const int est = rows.expected(), tn = (N + 255) / 256;
+  const long t256 = (long)((est + 255) / 256) * tn, t128 = (long)((est + 127) / 128) * tn;
+  const bf16_t *a = (const bf16_t *)A, *w = (const bf16_t *)W;
+  // same tile choice as gemm(): the largest tile that gives every compute unit work; four wavefronts where a unit takes several tiles
+  if (t256 >= 160) {
+    const bool four = t256 > 256;
+    const int slots = tn * (four ? 2 : 4), tm = (rows.cap + 255) / 256;
+    if ((size_t)rows.cap * slots * 12 > part_bytes) return false;
+    *n_slots = slots;
+    return four ? launch_pipe_epi<256, 4, EPI_CONF>(s, a, w, N, K, rows, part, slots, tm, tn, Warm())
+                : launch_pipe_epi<256, 8, EPI_CONF>(s, a, w, N, K, rows, part, slots, tm, tn, Warm());
+  }
+  if (t128 >= 160) {
+    const int slots = tn * 4, tm = (rows.cap + 127) / 128;
+    if ((size_t)rows.cap * slots * 12 > part_bytes) return false;
+    *n_slots = slots;
+    return launch_pipe_epi<128, 8, EPI_CONF>(s, a, w, N, K, rows, part, slots, tm, tn, Warm());
+  }
+  return false;
+}
+
 bool gemm_fuses_silu_mul(int dtype, const void *A, const void *W, int N, int K) {
   return dtype == FOCUS_BF16 && K % 64 == 0 && N % 2 == 0 && ((uintptr_t)A & 15) == 0 && ((uintptr_t)W & 15) == 0;
 }
@@ -663,15 +649,6 @@ void gemm(hipStream_t s, int dtype, const void *A, const void *W, int N, int K, 
     if (ok) return;
   }
   if (fits32 && choice == 256 && (four ? launch_pipe<256, 4>(s, A, W, N, K, rows, epilogue, out, ldo, warm) : launch_pipe<256, 8>(s, A, W, N, K, rows, epilogue, out, ldo, warm))) return;
-  if (fits32 && choice == 128 && (epilogue == EPI_ADD_F32 || epilogue == EPI_STORE) && getenv("FOCUS_KS")) {
-    // one round of 128 x 256 tiles: four wavefronts of 128 x 128 that split the k-steps of every slab (half the LDS reads per MFMA
-    // of eight wavefronts of 64 x 64)
-    const int tm = (rows.cap + 127) / 128, tn = (N + 255) / 256;
-    const bf16_t *a = (const bf16_t *)A, *w = (const bf16_t *)W;
-    const bool ok = epilogue == EPI_ADD_F32 ? launch_pipe_epi<128, 4, EPI_ADD_F32, 256, 2>(s, a, w, N, K, rows, out, ldo, tm, tn, warm)
-                                            : launch_pipe_epi<128, 4, EPI_STORE, 256, 2>(s, a, w, N, K, rows, out, ldo, tm, tn, warm);
-    if (ok) return;
-  }
   if (fits32 && choice == 128 && launch_pipe<128, 8>(s, A, W, N, K, rows, epilogue, out, ldo, warm)) return;
   if (fits32 && choice == 0 && scratch.ptr && N % 8 == 0 && rows.cap <= 128) {
     // one tile of rows: pure weight streaming.  The expert-projection kernel (two workgroups per CU, two weight slabs in

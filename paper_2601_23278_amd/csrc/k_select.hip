@@ -299,6 +299,31 @@ __global__ __launch_bounds__(256) void k_confidence_merge(const float *__restric
   argmax[r] = mi;
 }
 
+// Merge of the per-wavefront triples that the fused vocabulary projection leaves (gemm_conf_partials): one wavefront per row,
+// lane l folds slots l, l + 64, ... in ascending order, then the lanes are merged; equal maxima keep the lower column.
+__global__ __launch_bounds__(256) void k_confidence_slots(const float *__restrict__ part, int n_slots, Rows rows, float *conf, int32_t *argmax) {
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int M = rows.count ? min(*rows.count, rows.cap) : rows.cap;
+  if (r >= M) return;
+  const float *p = part + (size_t)r * n_slots * 3;
+  float m = -INFINITY, sum = 0.f;
+  int mi = 0x7fffffff;
+  for (int i = lane; i < n_slots; i += 64) conf_merge(p[3 * i], __float_as_int(p[3 * i + 2]), p[3 * i + 1], m, mi, sum);
+  for (int o = 32; o > 0; o >>= 1) {
+    const float om = __shfl_xor(m, o), os = __shfl_xor(sum, o);
+    const int oi = __shfl_xor(mi, o);
+    conf_merge(om, oi, os, m, mi, sum);
+  }
+  if (lane == 0) {
+    conf[r] = 1.0f / sum;
+    argmax[r] = mi;
+  }
+}
+
+void confidence_from_partials(hipStream_t s, const float *part, int n_slots, Rows rows, float *conf, int32_t *argmax) {
+  if (rows.cap > 0) k_confidence_slots<<<(rows.cap + 3) / 4, 256, 0, s>>>(part, n_slots, rows, conf, argmax);
+}
+
 void confidence(hipStream_t s, const float *logits, int vocab, Rows rows, float *conf, int32_t *argmax, Scratch scratch) {
   if (rows.cap <= 0) return;
   if (rows.cap <= 512 && vocab >= 16384 && scratch.ptr && scratch.bytes >= (size_t)rows.cap * kConfParts * 12) {

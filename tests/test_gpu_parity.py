@@ -403,6 +403,39 @@ def test_small_bf16_large_vocabulary_few_rows():
     compare_steps(small_bf16(vocab=20008, mask_token_id=20007, batch=3, steps=2), 2, 2e-2, exact=False)
 
 
+def test_small_bf16_confidence_fused_into_the_vocabulary_projection():
+    """Without a logits output the vocabulary projection reduces its tiles to (max, sum exp, arg-max) triples and the logits are
+    never written (Alg. 1 Decode_and_Verify).  Same step twice from the same state, with and without the logits output: arg-max
+    tokens identical, confidences equal up to the order of the exp sums, commits identical; and the fused result against the
+    oracle's confidences.  40 sequences x 8 rows and 33000 tokens give the projection enough tiles for the fused kernel; the odd
+    vocabulary leaves a partly filled last column tile."""
+    pk, runner = _pk()
+    wl = small_bf16(vocab=33000, mask_token_id=32999, batch=40, prefix_lo=40, prefix_hi=90)
+    cfg, W, pool, states, lens, tables, n_pages = oracle_batch(wl)
+    sess = runner.open_session(wl, DEV)
+    n, B = wl.batch, wl.block_size
+    full = Outs(pk, wl, n)
+    sess.focus.focus_step(n, out=full.struct)
+    g1 = full.host()
+    sess.focus.focus_prefill_kv(sess.prefix_lens, sess.page_tables, None)          # same block again
+    lean = {k: torch.zeros_like(v) for k, v in full.t.items() if k in ("tokens", "mask_bits", "n_decoded", "keep_bits", "cu_seqlens", "conf", "argmax")}
+    sess.focus.focus_step(n, out=pk.make_step_out(**lean))
+    torch.cuda.synchronize()
+    g2 = {k: v.cpu().numpy() for k, v in lean.items()}
+    T = int(g1["cu_seqlens"][n])
+    assert T == n * 8 and np.array_equal(g1["keep_bits"], g2["keep_bits"])
+    assert np.array_equal(g1["argmax"][:T], g2["argmax"][:T])
+    assert np.max(np.abs(g1["conf"][:T] - g2["conf"][:T]) / g1["conf"][:T]) < 1e-5
+    assert np.array_equal(g1["tokens"], g2["tokens"]) and np.array_equal(g1["mask_bits"], g2["mask_bits"])
+    keep = [positions_of(u64(k), B) for k in g2["keep_bits"]]
+    tr = fo.focus_step(cfg, W, pool, states, keep_override=keep)
+    assert relerr(g2["conf"][:T], tr.conf) <= 5 * 2e-2
+    top = np.sort(tr.logits, axis=1)
+    for r in range(T):        # the fused arg-max is (nearly) the oracle's
+        assert tr.logits[r][int(g2["argmax"][r])] >= top[r, -1] - 5 * 2e-2 * np.max(np.abs(tr.logits[r]))
+    sess.focus.focus_free()
+
+
 def test_small_bf16_block64_override_empty_and_full():
     wl = small_bf16(block_size=64, budget_mode=3, batch=4, steps=2)
     compare_steps(wl, 2, 2e-2, exact=False, k_override=[0, 64, 17, 1])
