@@ -251,6 +251,17 @@ __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// Lane exchanges inside a row of 16 lanes without LDS: CTRL is a data-parallel-primitive pattern (0xB1 / 0x4E: lanes l ^ 1 / l ^ 2
+// of a quad, 0x141: lane 7 - l of eight, 0x140: lane 15 - l of sixteen).  All four are permutations, so every lane has a source.
+template <int CTRL> __device__ __forceinline__ float lane_dpp(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
+}
+template <int CTRL> __device__ __forceinline__ void lane_max_step(float &m, int &mi) {
+  const float om = lane_dpp<CTRL>(m);
+  const int oi = __builtin_amdgcn_update_dpp(0, mi, CTRL, 0xF, 0xF, false);
+  if (om > m || (om == m && oi < mi)) { m = om; mi = oi; }     // equal maxima: the lower column
+}
+
 template <int BM, int NW, int EPI, int BN = 256>
 __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void k_gemm_pipe(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W, int N, int K,
                                                       Rows rows, void *out, int ldo, int tiles_m, int tiles_n, const void *warm,
@@ -444,42 +455,58 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void k_gemm_pipe(const bf
     return;
   }
   if (EPI == EPI_CONF) {
-    // per row: (maximum, sum exp(x - maximum), lowest column of the maximum) over this wavefront's WN columns.  A lane holds the
-    // TN values of one row that sit in column ecol of the TN column tiles; the 32 lanes of a lane half hold the same rows.
+    // per row: (maximum, sum exp(x - maximum), lowest column of the maximum) over this wavefront's WN columns.  The accumulators
+    // hold a row spread over 32 lanes; each 32 x WN patch goes through a private LDS area (the operand stages are free: every
+    // load has landed) and comes back with two lanes per row, each holding half of the row's columns in order, so that the
+    // reductions run inside a lane and one exchange with the neighbour lane finishes them.
+    constexpr int XS = WN + 4;                               // padded row: two lanes per row read 16-byte pieces
+    static_assert(NW * 32 * XS * 4 <= 2 * (BM + BN) * 128, "transpose area");
+    lds_barrier();                                           // everybody's loads have landed, nobody reads operands any more
+    float *xp = (float *)lds + wave * (32 * XS);
     const int slot = (n0 / BN) * WCOLS + wn / WN;
+    const int xrow = lane >> 1, xpart = lane & 1;
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float m = -INFINITY, sum = 0.f;
-        int mi = 0x7fffffff;
+      for (int j = 0; j < TN; ++j) {
+        const bool ok = n0 + wn + j * 32 + ecol < N;
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          const int gn = n0 + wn + j * 32 + ecol;
-          const float v = acc[i][j][r];
-          if (gn < N && v > m) { m = v; mi = gn; }          // ascending columns: the first maximum stays
-        }
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          const int gn = n0 + wn + j * 32 + ecol;
-          sum += gn < N ? __expf(acc[i][j][r] - m) : 0.f;
-        }
-#pragma unroll
-        for (int o = 16; o > 0; o >>= 1) {
-          const float om = __shfl_xor(m, o), os = __shfl_xor(sum, o);
-          const int oi = __shfl_xor(mi, o);
-          const float big = fmaxf(m, om);
-          const float fa = m == big ? 1.0f : __expf(m - big), fb = om == big ? 1.0f : __expf(om - big);
-          sum = sum * fa + os * fb;
-          if (om > m || (om == m && oi < mi)) mi = oi;
-          m = big;
-        }
-        const int gm = erow + i * 32 + 8 * (r >> 2) + (r & 3);
-        if (ecol == 0 && gm < M) {
-          float *p = (float *)out + ((size_t)gm * ldo + slot) * 3;
-          p[0] = m; p[1] = sum; p[2] = __int_as_float(mi);
-        }
+        for (int r = 0; r < 16; ++r)
+          xp[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * XS + j * 32 + ecol] = ok ? acc[i][j][r] : -INFINITY;
       }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+      const float4 *src = (const float4 *)(xp + xrow * XS + xpart * (WN / 2));
+      float4 v[WN / 8];
+#pragma unroll
+      for (int k = 0; k < WN / 8; ++k) v[k] = src[k];
+      float m = -INFINITY;
+      int mi = 0x7fffffff;
+      const int c0 = n0 + wn + xpart * (WN / 2);
+#pragma unroll
+      for (int k = 0; k < WN / 8; ++k) {                     // ascending columns: the first maximum stays
+        if (v[k].x > m) { m = v[k].x; mi = c0 + 4 * k; }
+        if (v[k].y > m) { m = v[k].y; mi = c0 + 4 * k + 1; }
+        if (v[k].z > m) { m = v[k].z; mi = c0 + 4 * k + 2; }
+        if (v[k].w > m) { m = v[k].w; mi = c0 + 4 * k + 3; }
+      }
+      lane_max_step<0xB1>(m, mi);                            // the row's other half (lane l ^ 1)
+      float sum = 0.f;
+      if (m > -INFINITY) {
+#pragma unroll
+        for (int k = 0; k < WN / 8; ++k) sum += __expf(v[k].x - m) + __expf(v[k].y - m) + __expf(v[k].z - m) + __expf(v[k].w - m);
+      }
+      sum += lane_dpp<0xB1>(sum);
+      const int gm = m0 + wm + i * 32 + xrow;
+      if (xpart == 0 && gm < M) {
+        float *p = (float *)out + ((size_t)gm * ldo + slot) * 3;
+        p[0] = m; p[1] = sum; p[2] = __int_as_float(mi);
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+      __builtin_amdgcn_wave_barrier();                       // the patch is rewritten by the next row tile
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+    }
     return;
   }
   if (EPI == EPI_ADD_F32 && inside) {
