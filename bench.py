@@ -311,20 +311,30 @@ def trace_summary(stats_csv: str, bench_log: str, tag: str, command: str):
         return s.replace("fk::", "")
     rows = [r for r in csv.DictReader(open(stats_csv)) if "fk::" in r["Name"] or "_ZN2fk" in r["Name"]]
     rows.sort(key=lambda r: -float(r["TotalDurationNs"]))
+    # per-dispatch durations (a kernel that serves two shapes, e.g. the O and the down projection, shows both in its quantiles)
+    per = {}
+    trace_csv = stats_csv.replace("_kernel_stats.csv", "_kernel_trace.csv")
+    if os.path.exists(trace_csv):
+        for r in csv.DictReader(open(trace_csv)):
+            per.setdefault(short(r["Kernel_Name"]), []).append((int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3)
+
+    def quant(n):
+        d = sorted(per.get(n, []))
+        return "%9.1f %9.1f %9.1f" % (d[len(d) // 10], d[len(d) // 2], d[(9 * len(d)) // 10]) if d else ""
     passes = line["steps"] + line["warmup"] + 1 + (1 if line["config"].get("row_hint") else 0)
     out = ["rocprofv3 kernel trace of bench.py, %s, one MI355X." % line["config"]["workload"],
            "Command (from /tmp, TMPDIR=/tmp):", "  " + command,
            "The run executes %d steps (%d warm-up, %d timed, 1 per-class timing pass%s); bench.py reported %.2f ms per step in the same run."
            % (passes, line["warmup"], line["steps"], ", 1 probe step for the row hint" if line["config"].get("row_hint") else "", line["ms_per_step"]),
            "Source: *_kernel_stats.csv (Calls, TotalDurationNs, AverageNs); library kernels only.\n",
-           "%-64s %8s %12s %10s" % ("kernel", "calls", "total_ms", "avg_us")]
+           "%-64s %8s %12s %10s %9s %9s %9s" % ("kernel", "calls", "total_ms", "avg_us", "p10_us", "p50_us", "p90_us")]
     tot = gemm = attn = 0.0
     for r in rows:
         n, t = short(r["Name"]), float(r["TotalDurationNs"])
         tot += t
         gemm += t if ("k_gemm" in n or "k_splitk" in n) else 0.0
         attn += t if "k_attn" in n else 0.0
-        out.append("%-64s %8s %12.3f %10.2f" % (n[:64], r["Calls"], t / 1e6, float(r["AverageNs"]) / 1e3))
+        out.append("%-64s %8s %12.3f %10.2f %s" % (n[:64], r["Calls"], t / 1e6, float(r["AverageNs"]) / 1e3, quant(n)))
     out.append("library kernels total: %.3f ms over %d steps = %.3f ms per step\n" % (tot / 1e6, passes, tot / 1e6 / passes))
     fl, nl = line["roofline"].get("flops_per_step"), line["roofline"]["launches"]
     kvb = line["attention_hbm"]["kv_bytes_per_step"]

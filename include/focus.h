@@ -144,7 +144,9 @@ typedef struct focus_step_out {
   float    *hidden_full;    /* [n * B, hidden]  residual stream entering layer e: row b * B + p, or, with the
                                intra-block cache, the rows of the positions that are not frozen, packed in batch order */
   float    *hidden_packed;  /* [n * B, hidden]  first T' rows valid: residual stream after the last layer */
-  float    *logits;         /* [n * B, vocab]   first T' rows valid */
+  float    *logits;         /* [n * B, vocab]   first T' rows valid.  NULL (the normal case): a bf16 model with enough rows for
+                               the tiled projection never writes the logits; the projection's epilogue reduces each tile to
+                               (max, sum exp, arg-max) and conf / argmax come from those */
   int32_t  *route_experts;  /* [n_layers, max_batch * B, k]  mixture-of-experts layers: the experts row b * B + p used, in the
                                order of their weights; written for the rows that ran in the layer, other entries untouched */
   float    *route_weights;  /* [n_layers, max_batch * B, k]  their mixing weights (route_scale included) */
@@ -161,11 +163,14 @@ typedef struct focus_seq_state {
   int32_t  tokens[FOCUS_MAX_BLOCK];
 } focus_seq_state;
 
-/* Sizes the caller must allocate.  Both need only the shape members of cfg. */
+/* Infrastructure (no passage of the paper: the paper's engine keeps this state in its serving framework, App. E.3.1 only lists
+ * what the state is).  Sizes the caller must allocate; both need only the shape members of cfg.  The workspace holds the
+ * per-slot state of App. E.3.1 (masked / processed / frozen sets, token_sum, total_steps, block tokens, prefix lengths, page
+ * tables), the rotary table and every activation buffer of a step. */
 int focus_workspace_bytes(const focus_config *cfg, size_t *bytes);
 int focus_kv_pool_bytes(const focus_config *cfg, size_t *bytes);
 
-/* Creates a context over borrowed device memory.  Builds the rotary table and zeroes the slot state
+/* Infrastructure.  Creates a context over borrowed device memory.  Builds the rotary table and zeroes the slot state
  * (synchronous).  EINVAL: bad shape / unsupported switch / NULL; ENOMEM: a buffer is too small. */
 int focus_init(const focus_config *cfg, const focus_weights *weights, void *kv_pool, size_t kv_pool_bytes,
                void *workspace, size_t workspace_bytes, focus_ctx **out);
@@ -277,11 +282,12 @@ int focus_commit(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32_t 
                  const uint64_t *keep_bits, const int32_t *cu_seqlens, const float *conf,
                  const int32_t *argmax, const focus_step_out *out);
 
-/* Debug access to one slot's state (synchronous device copies). */
+/* Infrastructure for tests and schedulers: one slot's block state (the fields App. E.3.1 names, plus the block's tokens) read
+ * from / written to the device (synchronous copies; not for use between the steps of a timed loop). */
 int focus_get_state(focus_ctx *ctx, int32_t slot, focus_seq_state *state);
 int focus_set_state(focus_ctx *ctx, int32_t slot, const focus_seq_state *state);
 
-/* Per-kernel-class device time of the last focus_step.  With timing enabled every kernel launch of a step
+/* Infrastructure for measurement (no passage).  Per-kernel-class device time of the last focus_step.  With timing enabled every kernel launch of a step
  * is bracketed by a pair of HIP events on the step's stream (this adds small gaps between kernels, so time
  * whole steps with timing off).  focus_get_kernel_time synchronises the stream and returns the summed
  * duration and the number of launches of one class. */
@@ -300,8 +306,9 @@ enum { FOCUS_KC_GEMM = 0,      /* dense projections: QKV, O, gate/up, down, lm_h
 int focus_set_timing(focus_ctx *ctx, int32_t enable);
 int focus_get_kernel_time(focus_ctx *ctx, int32_t kernel_class, float *total_ms, int32_t *launches);
 
+/* Infrastructure.  Destroys the context; the borrowed buffers stay the caller's. */
 int focus_free(focus_ctx *ctx);
-/* Text of the last error of ctx, or of the last failed call without a context when ctx is NULL. */
+/* Infrastructure.  Text of the last error of ctx, or of the last failed call without a context when ctx is NULL. */
 const char *focus_last_error(const focus_ctx *ctx);
 
 #ifdef __cplusplus
