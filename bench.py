@@ -343,6 +343,14 @@ def trace_summary(stats_csv: str, bench_log: str, tag: str, command: str):
                    "2.5 PFLOP/s bf16 MFMA peak; average launch %.1f us.  bench.py's event pairs in the same run: %.2f ms, %.0f TFLOP/s, average launch %.1f us."
                    % (nl, gemm / 1e6 / passes, fl / 1e12, fl / (gemm / 1e9 / passes) / 1e12, 100 * fl / (gemm / 1e9 / passes) / 2.5e15,
                       gemm / 1e3 / passes / nl, line["kernel_classes_ms"]["gemm"]["ms"], line["roofline"]["achieved"], 1e3 * line["roofline"]["avg_launch_ms"]))
+    rl = line["roofline"]
+    if rl["bound"] == "hbm":
+        grp = sum(float(r["TotalDurationNs"]) for r in rows if "k_group_gemm" in r["Name"])
+        out.append("bench.py's roofline of this run (event pairs): %s: %.1f GB per step in %.2f ms over %d launches -> %.0f GB/s = %.1f %% of the 8 TB/s HBM peak."
+                   % (rl["kernel"], rl["bytes_per_step"] / 1e9, rl["avg_launch_ms"] * rl["launches"], rl["launches"], rl["achieved"], 100 * rl["frac"]))
+        if line["config"].get("experts"):
+            out.append("Kernel trace of the same class (k_group_gemm<1> = gate/up + SiLU*up, <0> = down): %.2f ms per step -> %.0f GB/s."
+                       % (grp / 1e6 / passes, rl["bytes_per_step"] / (grp / 1e9 / passes) / 1e9))
     out.append("Attention class (k_attn_*): %.2f ms per step for %.1f GB of K/V -> %.2f TB/s = %.1f %% of the 8 TB/s HBM peak (event pairs: %.2f ms)."
                % (attn / 1e6 / passes, kvb / 1e9, kvb / (attn / 1e9 / passes) / 1e12, 100 * kvb / (attn / 1e9 / passes) / 8e12, line["kernel_classes_ms"]["attention"]["ms"]))
     for name, ph in line["phases"].items():
