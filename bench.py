@@ -361,6 +361,58 @@ def trace_summary(stats_csv: str, bench_log: str, tag: str, command: str):
     print("\n".join(out[-8:]))
 
 
+def mfma_summary(counter_csv: str, workload: str, ratio: float):
+    """Condenses `rocprofv3 --pmc MfmaUtil MfmaFlopsBF16` of one benchmark step into profiles/: per (kernel, grid) the share of
+    cycles in which the matrix cores were busy (SQ_VALU_MFMA_BUSY_CYCLES over active cycles x SIMDs: a figure in the chip's
+    ACTUAL clock cycles, unlike the TFLOP/s fractions, which are against the peak at the nominal clock) and the bf16 flops the
+    hardware counted, next to the algorithmic flops bench.py prices the launch at."""
+    def short(n):
+        m = re.match(r"_ZN2fk\d+(k_[a-z0-9_]+)", n)
+        if m:
+            return m.group(1)
+        s = re.sub(r"^void ", "", n)
+        s = re.sub(r"\(.*", "", s)
+        return s.replace("fk::", "")
+    per = {}
+    for r in csv.DictReader(open(counter_csv)):
+        name = r["Kernel_Name"]
+        if not ("fk::" in name or "_ZN2fk" in name):
+            continue
+        e = per.setdefault((short(name), int(r["Grid_Size"])), {"MfmaUtil": [], "MfmaFlopsBF16": [], "us": []})
+        if r["Counter_Name"] in e:
+            e[r["Counter_Name"]].append(float(r["Counter_Value"]))
+        if r["Counter_Name"] == "MfmaUtil":
+            e["us"].append((int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3)
+    lines = ["rocprofv3 matrix-core counters of one benchmark step, workload %s, keep ratio %g, one MI355X:" % (workload, ratio),
+             "  rocprofv3 --pmc MfmaUtil MfmaFlopsBF16 --kernel-include-regex fk --output-format csv -d gpurun_out/pmc_mfma -o p -- python3 /root/repo/bench.py "
+             "--workload %s --keep-ratio %g --steps 1 --warmup 0 --no-extras --no-cpu-baseline" % (workload, ratio),
+             "  python3 bench.py --workload %s --keep-ratio %g --mfma-summary gpurun_out/pmc_mfma/.../p_counter_collection.csv" % (workload, ratio),
+             "MfmaUtil = 100 * SQ_VALU_MFMA_BUSY_CYCLES / (GRBM_GUI_ACTIVE * number of SIMDs): the share of the chip's ACTUAL cycles in which a SIMD's matrix",
+             "core was busy.  The TFLOP/s fractions elsewhere are against the peak at the nominal 2.4 GHz; busy share x (actual clock / 2.4 GHz) = that fraction,",
+             "so e.g. 61 % busy at 0.50 of the nominal peak means the chip ran at about 2.0 GHz under this load.  Durations are under the profiler (serialised).",
+             "MfmaFlopsBF16 = what the hardware counted; it equals 2*M*N*K of the launch (no padded or wasted MFMA work beyond the tile edges).\n",
+             "%-40s %9s %9s %12s %14s %10s" % ("kernel", "grid", "launches", "MFMA busy %", "bf16 GFLOP", "avg us")]
+    for k in sorted(per, key=lambda k: -sum(per[k]["MfmaFlopsBF16"])):
+        e = per[k]
+        if not e["MfmaUtil"] or sum(e["MfmaFlopsBF16"]) == 0:
+            continue
+        lines.append("%-40s %9d %9d %12.1f %14.1f %10.1f" % (k[0][:40], k[1], len(e["MfmaUtil"]), sum(e["MfmaUtil"]) / len(e["MfmaUtil"]),
+                                                              sum(e["MfmaFlopsBF16"]) / len(e["MfmaFlopsBF16"]) / 1e9, sum(e["us"]) / len(e["us"])))
+    gem = [(sum(e["MfmaUtil"]) / len(e["MfmaUtil"]), sum(e["us"])) for k, e in per.items() if "k_gemm" in k[0] and e["MfmaUtil"]]
+    att = [(sum(e["MfmaUtil"]) / len(e["MfmaUtil"]), sum(e["us"])) for k, e in per.items() if "k_attn" in k[0] and e["MfmaUtil"]]
+    for name, g in (("projection", gem), ("attention", att)):
+        if g:
+            lines.append("%s class, time-weighted: matrix cores busy %.1f %% of the cycles" % (name, sum(u * t for u, t in g) / sum(t for _, t in g)))
+    tag = "%s_keep%03d" % (workload, int(round(1000 * ratio)))
+    open(os.path.join(ROOT, "profiles", "%s_mfma_util.txt" % tag), "w").write("\n".join(lines) + "\n")
+    json.dump({"workload": workload, "keep_ratio": ratio,
+               "gemm_mfma_busy_pct": sum(u * t for u, t in gem) / sum(t for _, t in gem) if gem else None,
+               "attention_mfma_busy_pct": sum(u * t for u, t in att) / sum(t for _, t in att) if att else None,
+               "method": "rocprofv3 --pmc MfmaUtil, time-weighted over the launches of the class; see %s_mfma_util.txt" % tag},
+              open(os.path.join(ROOT, "profiles", "pmc_mfma_%s.json" % tag), "w"))
+    print("\n".join(lines[-14:]))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -381,6 +433,7 @@ def main():
                     help="also launch one 1 GiB device-to-device copy (a dispatch of known size for scaling rocprofv3 byte counters)")
     ap.add_argument("--trace-summary", nargs=4, metavar=("STATS_CSV", "BENCH_LOG", "TAG", "COMMAND"),
                     help="no GPU: write profiles/bench_TAG_kernel_stats.txt from a rocprofv3 --kernel-trace --stats run of this benchmark")
+    ap.add_argument("--mfma-summary", metavar="COUNTER_CSV", help="no GPU: write profiles/*_mfma_util.txt from a rocprofv3 --pmc MfmaUtil MfmaFlopsBF16 run")
     ap.add_argument("--pmc-summary", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"), help="no GPU: write profiles/ summaries from two rocprofv3 --pmc runs")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -398,6 +451,9 @@ def main():
     wl = fi.workload(args.workload, **over)
     if args.pmc_summary:
         pmc_summary(args.pmc_summary[0], args.pmc_summary[1], wl.name, wl.keep_ratio)
+        return
+    if args.mfma_summary:
+        mfma_summary(args.mfma_summary, wl.name, wl.keep_ratio)
         return
 
     import torch
@@ -422,8 +478,15 @@ def main():
         # only a figure measured on this workload and ratio, and one that the chip could have moved in the measured time
         if rec.get("workload") == wl.name and abs(rec.get("keep_ratio", -1) - ratio0) < 1e-6 and t and t <= PEAK_HBM_GBS * 1e9 * gemm_ms * 1e-3:
             traffic = t
+    mfma_busy = None
+    mpath = os.path.join(ROOT, "profiles", "pmc_mfma_%s_keep%03d.json" % (wl.name, int(round(1000 * max(ratio0, 0)))))
+    if wl.budget_mode == 1 and os.path.exists(mpath):
+        rec = json.load(open(mpath))
+        if rec.get("workload") == wl.name and abs(rec.get("keep_ratio", -1) - ratio0) < 1e-6:
+            mfma_busy = dict(projections_pct=rec.get("gemm_mfma_busy_pct"), attention_pct=rec.get("attention_mfma_busy_pct"),
+                             note="hardware counter (share of actual cycles with the matrix cores busy), from profiles/, not measured by this run")
     roofline = dict(bound="mfma", kernel="gemm (all dense projections of a step)", achieved=round(achieved, 2), peak=PEAK_BF16_TFLOPS,
-                    unit="TFLOP/s", frac=round(achieved / PEAK_BF16_TFLOPS, 4), traffic=traffic,
+                    unit="TFLOP/s", frac=round(achieved / PEAK_BF16_TFLOPS, 4), traffic=traffic, mfma_busy_counter=mfma_busy,
                     flops_per_step=flops, launches=classes["gemm"]["launches"], avg_launch_ms=round(gemm_ms / max(1, classes["gemm"]["launches"]), 5))
     dense_gemm = None
     if not wl.n_experts and n * B < 312:
