@@ -223,6 +223,14 @@ class Runner:
             gbs = nbytes / (ms * 1e-3) / 1e9 if ms > 0 else 0.0
             phases[name] = dict(GBs=round(gbs, 1), frac_of_hbm_peak=round(gbs / PEAK_HBM_GBS, 4), ms=ms, bytes_per_step=nbytes,
                                 launches=classes[name]["launches"])
+        # matrix work of the attention: QK^T and PV, 4 * D flop per (query row, query head, visible token)
+        counts = (self.cu[1:] - self.cu[:-1]).cpu().tolist()
+        e, L = wl.evict_layer, wl.n_layers
+        lens = self.sess.prefix_lens
+        fl_att = 4.0 * wl.n_q_heads * wl.head_dim * sum((e * B + (L - e) * q) * (l + B) for q, l in zip(counts, lens))
+        a_ms = classes["attention"]["ms"]
+        phases["attention"]["TFLOPs"] = round(fl_att / (a_ms * 1e-3) / 1e12, 1) if a_ms > 0 else 0.0
+        phases["attention"]["frac_of_mfma_peak"] = round(phases["attention"]["TFLOPs"] / PEAK_BF16_TFLOPS, 4)
         res["phases"] = phases
         return res
 

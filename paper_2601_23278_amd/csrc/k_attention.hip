@@ -212,41 +212,44 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_mfma(AttnArgs a) {
     if (more) issue_k(tile + 1);
     bf16x8 pf[4];
     if (wave_has_rows) {
-      // scale, mask, running max
+      // mask, running maximum (of the raw scores: the scale is positive and is folded into the exponent's multiply-add)
       const bool need_mask = tile * 64 + 64 > L;
       float mx = -INFINITY;
 #pragma unroll
       for (int u = 0; u < 2; ++u)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          float s = sacc[u][r] * sc;
+          float s = sacc[u][r];
           if (need_mask) {
             const int tok = tile * 64 + 32 * u + sigma32(8 * (r >> 2) + 4 * half + (r & 3));
             const bool ok = tok < L || (tok < total && ((vis >> (tok - L)) & 1ull));
             s = ok ? s : -INFINITY;
+            sacc[u][r] = s;
           }
-          sacc[u][r] = s;
           mx = fmaxf(mx, s);
         }
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      mx = fmaxf(mx, __shfl_xor(mx, 32)) * sc;
       const float m_new = fmaxf(m, mx);
       const float m_use = m_new == -INFINITY ? 0.f : m_new;
-      const float corr = exp2f(m - m_use);
+      const float corr = __builtin_amdgcn_exp2f(m - m_use);
       m = m_new;
       float ls = 0.f;
 #pragma unroll
       for (int u = 0; u < 2; ++u)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          float p = exp2f(sacc[u][r] - m_use);
+          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[u][r], sc, -m_use));
           ls += p;
           pf[2 * u + (r >> 3)][r & 7] = (bf16_t)p;
         }
       l = l * corr + ls;
+      // the 64 output accumulators are rescaled only when some row's maximum moved (after the first tiles it rarely does)
+      if (__builtin_amdgcn_ballot_w64(corr != 1.0f) != 0) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[i][r] *= corr;
+          for (int r = 0; r < 16; ++r) oacc[i][r] *= corr;
+      }
     }
     if (more) __builtin_amdgcn_s_waitcnt(vmcnt_imm(IPW)); else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));   // V(tile) is in LDS
     __builtin_amdgcn_s_barrier();
