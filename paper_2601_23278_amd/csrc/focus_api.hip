@@ -288,8 +288,10 @@ void swiglu_ffn(focus_ctx *c, hipStream_t s, const RowSet &rs, const void *norme
 void moe_ffn(focus_ctx *c, hipStream_t s, int l, const RowSet &rs, float *resid, const void *normed);
 
 // attention -> O projection (+residual) -> rmsnorm -> feed-forward (+residual).
+// imp_partial: Eq. 2 of this layer is wanted at that address ([n, H_q, B] per-head sums); the attention launch computes it on the
+// way when it can, else the stand-alone kernel runs.
 void layer_rest(focus_ctx *c, hipStream_t s, int l, const RowSet &rs, float *resid, const void *q, int q_stride,
-                const uint64_t *vis_by_b) {
+                const uint64_t *vis_by_b, float *imp_partial = nullptr) {
   const focus_config &g = c->cfg;
   const int q_w = g.n_q_heads * g.head_dim;
   void *normed = c->at<char>(c->plan.off_normed), *attn = c->at<char>(c->plan.off_attn);
@@ -304,7 +306,12 @@ void layer_rest(focus_ctx *c, hipStream_t s, int l, const RowSet &rs, float *res
     a.warm = fk::Warm{c->w_o[l], (size_t)g.hidden * q_w * esize(g.dtype)};
     attention_split(c, rs.n_seq, rs.rows.cap, &a.chunk, &a.launch_splits);
     a.max_splits = a.launch_splits;
-    fk::attention(s, a); }
+    a.imp_partial = imp_partial; a.imp_pool_k = g.maxpool_k;
+    if (fk::attention(s, a)) imp_partial = nullptr; }
+  if (imp_partial) {
+    Timed t(c, s, FOCUS_KC_IMPORTANCE);
+    fk::importance(s, g.dtype, q, rs.cu, rs.n_seq, g.block_size, g.n_q_heads, g.n_kv_heads, g.head_dim, g.maxpool_k, rs.ri.seq_slot, c->slots(), c->kv_layer(l), imp_partial);
+  }
   { Timed t(c, s, FOCUS_KC_GEMM); fk::gemm(s, g.dtype, attn, c->w_o[l], g.hidden, q_w, rs.rows, fk::EPI_ADD_F32, resid, g.hidden, fk::Warm(), c->scratch()); }
   { Timed t(c, s, FOCUS_KC_POINTWISE); fk::rmsnorm(s, g.dtype, resid, c->mlp_norm[l], normed, g.hidden, g.rms_eps, rs.rows); }
   const size_t qkv_bytes = (size_t)(g.n_q_heads + 2 * g.n_kv_heads) * g.head_dim * g.hidden * esize(g.dtype);
@@ -692,11 +699,8 @@ int focus_step(focus_ctx *ctx, void *hip_stream, int32_t n_seq, const int32_t *s
     fk::embed(s, g.dtype, ctx->embed, g.hidden, full.rows, full.ri, st, g.mask_token_id, resid); }
   for (int l = 0; l < e; ++l) {
     layer_qkv(ctx, s, l, full, resid);
-    if (l == e - 1 && g.importance_mode == 0) {
-      Timed t(ctx, s, FOCUS_KC_IMPORTANCE);
-      fk::importance(s, g.dtype, qkv, cu_full, n_seq, B, g.n_q_heads, g.n_kv_heads, g.head_dim, g.maxpool_k, seq_slot, st, ctx->kv_layer(l), partial);
-    }
-    layer_rest(ctx, s, l, full, resid, qkv, qkv_w, nullptr);
+    // Eq. 2 of layer e - 1 rides on that layer's attention pass over the whole block
+    layer_rest(ctx, s, l, full, resid, qkv, qkv_w, nullptr, l == e - 1 && g.importance_mode == 0 ? partial : nullptr);
   }
   if (o.hidden_full)
     (void)hipMemcpyAsync(o.hidden_full, resid, (size_t)T0 * g.hidden * 4, hipMemcpyDeviceToDevice, s);

@@ -131,8 +131,14 @@ struct AttnArgs {
   int chunk, max_splits, launch_splits;
   const int32_t *order;          // batch entries sorted by descending prefix length (longest first), or null
   Warm warm;                     // weights of the projection that follows (bf16 kernel only)
+  // Eq. 2 fused into this pass (the layer below the eviction layer, whose attention runs over the whole block anyway): when not
+  // null, the workgroup that holds a sequence's last K/V range also reduces the in-block score tile of its query heads to
+  // imp_partial[b, h, j] (the layout importance() writes).  attention() says whether it did.
+  float *imp_partial = nullptr;
+  int imp_pool_k = 3;
 };
-void attention(hipStream_t s, const AttnArgs &a);
+// Returns true when imp_partial was asked for and has been written by the attention launch itself.
+bool attention(hipStream_t s, const AttnArgs &a);
 // Eq. 2 per (sequence, query head): partial[b, h, j] = sum over the sequence's query rows (rows cu[b] .. cu[b + 1] of the
 // fused qkv buffer, after the rotary embedding) of the pooled block-local softmax over the B in-block keys, which
 // are read from the layer's K cache (every row's key has been written there; frozen positions keep theirs).

@@ -89,15 +89,24 @@ constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) |
 #define FK_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 #define FK_GLB_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
 
-template <int NW>
+// BJ > 0: the kernel also reduces the in-block score tile to the token importance of Eq. 2 (blocks of up to BJ positions); its LDS
+// is then dynamic: the two tile buffers, a score patch of 32 x (BJ + 1) floats per wavefront, and per-wavefront column sums.
+template <int NW, int BJ = 0>
 __global__ __launch_bounds__(NW * 64, 2) void k_attn_mfma(AttnArgs a) {
   constexpr int D = 128, P = 64, IPW = 16 / NW;       // 1 KB load instructions per wavefront for K, and for V
-  __shared__ __attribute__((aligned(1024))) unsigned char lds[32768];
+  constexpr bool IMP = BJ > 0;
+  __shared__ __attribute__((aligned(1024))) unsigned char lds_fixed[IMP ? 1024 : 32768];
+  extern __shared__ __attribute__((aligned(1024))) unsigned char lds_imp[];
+  unsigned char *const lds = IMP ? lds_imp : lds_fixed;
   const int Hkv = a.kv.n_kv_heads, Hq = a.n_q_heads, g = Hq / Hkv;
   const int bo = blockIdx.x / Hkv, hk = blockIdx.x % Hkv, split = blockIdx.y;
   const int b = a.order ? a.order[bo] : bo;
   const int r0 = a.cu[b], nr = a.cu[b + 1] - r0;
-  if (nr <= 0) return;
+  if (nr <= 0) {
+    if (BJ > 0 && a.imp_partial && split == 0)           // a sequence without query rows: its importance sums are zero
+      for (int i = threadIdx.x; i < g * a.ri.B; i += NW * 64) a.imp_partial[((size_t)b * Hq + hk * g) * a.ri.B + i] = 0.f;
+    return;
+  }
   const int slot = slot_of(a.ri.seq_slot, b, a.st);
   const int L = a.st.prefix_len[slot], total = L + a.ri.B;
   // Splits that have tokens: the sequence's own length decides (it is read here, on the device), bounded by the number of
@@ -110,6 +119,12 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_mfma(AttnArgs a) {
   const uint64_t vis = a.vis_by_b ? a.vis_by_b[b] : ~0ull;
   const int32_t *pt = a.st.page_table + (size_t)slot * a.st.table_stride;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5, col = lane & 31;
+  // fused importance: only the workgroup of the last K/V range of the sequence (it is the one that ends with the block's tokens)
+  const bool do_imp = IMP && a.imp_partial != nullptr && split == nsplit - 1;
+  float *const imp_scores = (float *)(lds + 32768) + wave * 32 * (BJ + 1);              // [32 pairs][BJ + 1]
+  float *const imp_wsum = (float *)(lds + 32768) + NW * 32 * (BJ + 1);                  // [NW][g][BJ]
+  if (do_imp)
+    for (int i = tid; i < NW * g * BJ; i += NW * 64) imp_wsum[i] = 0.f;                  // (barriers of the tile loop order this)
 
   // Tiles go from global memory straight into LDS (global_load_lds_dwordx4: lane l of an instruction fills
   // the 16-byte slot l of a 1 KB LDS block), so the swizzle is applied on the global side: the lane that owns
@@ -271,7 +286,7 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_mfma(AttnArgs a) {
   }
 
   const float l_tot = l + __shfl_xor(l, 32);
-  if (!qvalid) continue;
+  if (qvalid) {
   if (nsplit == 1) {
     const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
     bf16_t *orow = (bf16_t *)a.out + (size_t)qrow * Hq * D + (size_t)qhead * D;
@@ -299,7 +314,89 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_mfma(AttnArgs a) {
       a.part_ml[pi * 2 + 1] = l_tot;
     }
   }
+  }   // qvalid
+  if constexpr (IMP) {
+    if (do_imp) {
+      // Eq. 2 for this pass's (row, head) pairs: scores against the block's own B keys (the one or two tiles that hold positions
+      // L .. L + B - 1 are fetched again: they were just streamed and sit in the L2), MaxPool1D along the keys, softmax over the
+      // B keys, sums over the rows of every head.  The query fragments are still in registers.
+      const int B = a.ri.B, tb0 = L / 64, tb1 = (total - 1) / 64;
+      for (int tile = tb0; tile <= tb1; ++tile) {
+        __builtin_amdgcn_s_barrier();                      // the K buffer is free
+        const unsigned char *pg = pool + (size_t)__builtin_amdgcn_readfirstlane(pt[tile]) * page_bytes + k_head;
+#pragma unroll
+        for (int q = 0; q < IPW; ++q)
+          __builtin_amdgcn_global_load_lds(FK_GLB_PTR(pg + gk[q]), FK_LDS_PTR(Ks + (wave * IPW + q) * 1024), 16, 0, 0);
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        if (wave_has_rows) {
+#pragma unroll
+          for (int u = 0; u < 2; ++u) {
+            f32x16 sc2;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sc2[r] = 0.f;
+            const int tl = 32 * u + sigma32(col);
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+              const int ch = 2 * ks + half;
+              bf16x8 kf = *(const bf16x8 *)(Ks + tl * 256 + ((ch ^ (tl & 15)) << 4));
+              sc2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sc2, 0, 0, 0);
+            }
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int j = tile * 64 + 32 * u + sigma32(8 * (r >> 2) + 4 * half + (r & 3)) - L;
+              if (j >= 0 && j < B) imp_scores[col * (BJ + 1) + j] = sc2[r] * sc;     // log2 domain
+            }
+          }
+        }
+        asm volatile("" ::: "memory");
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+      if (wave_has_rows) {
+        float row[BJ];
+#pragma unroll
+        for (int j = 0; j < BJ; ++j) row[j] = j < B ? imp_scores[col * (BJ + 1) + j] : -INFINITY;
+        float mrow = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < BJ; ++j) mrow = fmaxf(mrow, row[j]);                     // the pooled row has the same maximum
+        float pooled[BJ], sum = 0.f;
+#pragma unroll
+        for (int j = 0; j < BJ; ++j) {
+          float v = row[j];
+          if (a.imp_pool_k == 3) {
+            if (j > 0) v = fmaxf(v, row[j - 1]);
+            if (j + 1 < BJ) v = fmaxf(v, row[j + 1]);
+          }
+          v = j < B ? __builtin_amdgcn_exp2f(v - mrow) : 0.f;                        // no position beyond the block takes part
+          pooled[j] = v;
+          sum += v;
+        }
+        const float inv = qvalid ? 1.0f / sum : 0.f;                                // lanes without a pair add nothing
+#pragma unroll
+        for (int j = 0; j < BJ; ++j) {
+          float v = pooled[j] * inv;
+          for (int o = g; o < 32; o <<= 1) v += __shfl_xor(v, o);                    // over the rows: lanes with the same col % g
+          if (half == 0 && col < g && j < B) imp_wsum[(wave * g + col) * BJ + j] += v;
+        }
+      }
+    }
+  }
   }   // passes
+  if constexpr (IMP) {
+    if (do_imp) {
+      __syncthreads();
+      const int B = a.ri.B;
+      for (int i = tid; i < g * BJ; i += NW * 64) {
+        const int hq = i / BJ, j = i % BJ;
+        float v = 0.f;
+        for (int w = 0; w < NW; ++w) v += imp_wsum[(w * g + hq) * BJ + j];           // wavefront order: reproducible
+        if (j < B) a.imp_partial[((size_t)b * Hq + hk * g + hq) * B + j] = v;
+      }
+    }
+  }
   // the last workgroups to start (the shortest sequences), once through their own K/V, pull the next projection's
   // weights into the memory-side cache: any earlier and the K/V stream would push them out again
   const unsigned warm_acc = warm_touch(a.warm.ptr, a.warm.bytes, NW * 64);
@@ -329,19 +426,43 @@ __global__ __launch_bounds__(128) void k_attn_combine(AttnArgs a) {
   ((bf16_t *)a.out)[((size_t)r * a.n_q_heads + hq) * 128 + d] = (bf16_t)(den > 0.f ? num / den : 0.f);
 }
 
-void attention(hipStream_t s, const AttnArgs &a) {
-  if (a.rows.cap <= 0 || a.n_seq <= 0) return;
+template <int NW, int BJ>
+static bool launch_attn_imp(hipStream_t s, dim3 grid, const AttnArgs &a, int g) {
+  const int bytes = 32768 + NW * 32 * (BJ + 1) * 4 + NW * g * BJ * 4;
+  static int allowed = 0;                // LDS beyond 64 KB has to be allowed once per kernel
+  if (bytes > allowed) {
+    if (hipFuncSetAttribute((const void *)k_attn_mfma<NW, BJ>, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess) return false;
+    allowed = bytes;
+  }
+  k_attn_mfma<NW, BJ><<<grid, NW * 64, bytes, s>>>(a);
+  return true;
+}
+
+bool attention(hipStream_t s, const AttnArgs &a) {
+  if (a.rows.cap <= 0 || a.n_seq <= 0) return false;
   const int g = a.n_q_heads / a.kv.n_kv_heads;
   const bool mfma = a.dtype == FOCUS_BF16 && a.kv.head_dim == 128 && a.kv.page_size == 64 && a.q_stride % 8 == 0 && a.part_o != nullptr;
   if (mfma) {
     dim3 grid(a.n_seq * a.kv.n_kv_heads, a.launch_splits);
     const int R = a.max_rows_per_seq * g;
-    if (R <= 32) k_attn_mfma<1><<<grid, 64, 0, s>>>(a);
-    else if (R <= 64) k_attn_mfma<2><<<grid, 128, 0, s>>>(a);
-    else if (R <= 128) k_attn_mfma<4><<<grid, 256, 0, s>>>(a);
-    else k_attn_mfma<8><<<grid, 512, 0, s>>>(a);
+    bool fused = false;
+    // importance rides along when the group size divides the 32 pairs of a wavefront (rows of one head are then the lanes with
+    // equal lane % g) and the score patches fit the LDS
+    if (a.imp_partial && (g == 1 || g == 2 || g == 4 || g == 8) && a.ri.B <= 64) {
+      const bool small = a.ri.B <= 32;
+      if (R <= 32) fused = small ? launch_attn_imp<1, 32>(s, grid, a, g) : launch_attn_imp<1, 64>(s, grid, a, g);
+      else if (R <= 64) fused = small ? launch_attn_imp<2, 32>(s, grid, a, g) : launch_attn_imp<2, 64>(s, grid, a, g);
+      else if (R <= 128) fused = small ? launch_attn_imp<4, 32>(s, grid, a, g) : launch_attn_imp<4, 64>(s, grid, a, g);
+      else fused = small ? launch_attn_imp<8, 32>(s, grid, a, g) : launch_attn_imp<8, 64>(s, grid, a, g);
+    }
+    if (!fused) {
+      if (R <= 32) k_attn_mfma<1><<<grid, 64, 0, s>>>(a);
+      else if (R <= 64) k_attn_mfma<2><<<grid, 128, 0, s>>>(a);
+      else if (R <= 128) k_attn_mfma<4><<<grid, 256, 0, s>>>(a);
+      else k_attn_mfma<8><<<grid, 512, 0, s>>>(a);
+    }
     if (a.launch_splits > 1) k_attn_combine<<<dim3(a.rows.cap, a.n_q_heads), 128, 0, s>>>(a);
-    return;
+    return fused;
   }
   dim3 grid(a.rows.cap, a.n_q_heads);
   const int ne = a.kv.head_dim / 64;
@@ -352,6 +473,7 @@ void attention(hipStream_t s, const AttnArgs &a) {
     if (ne == 1) k_attn_rowwave<bf16_t, 1><<<grid, 64, 0, s>>>((const bf16_t *)a.q, a.q_stride, a.n_q_heads, a.rows, a.ri, a.st, a.vis_by_b, a.kv, (bf16_t *)a.out);
     else k_attn_rowwave<bf16_t, 2><<<grid, 64, 0, s>>>((const bf16_t *)a.q, a.q_stride, a.n_q_heads, a.rows, a.ri, a.st, a.vis_by_b, a.kv, (bf16_t *)a.out);
   }
+  return false;
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -43,7 +43,7 @@ def gpu_step(pk, sess, wl, sample_ids, k_override=None, keep_rows_of=None):
     n, B, h, V = wl.batch, wl.block_size, wl.hidden, wl.vocab
     z = lambda *s, dt=torch.float32: torch.zeros(*s, dtype=dt, device=DEV)
     t = dict(tokens=z(n, B, dt=torch.int32), mask_bits=z(n, dt=torch.int64), n_decoded=z(n, dt=torch.int32),
-             importance=z(n, B), delta_I=z(n, B), K=z(n, dt=torch.int32), keep_bits=z(n, dt=torch.int64),
+             importance=z(n, B), importance_prev=z(n, B), delta_I=z(n, B), K=z(n, dt=torch.int32), keep_bits=z(n, dt=torch.int64),
              cu_seqlens=z(n + 1, dt=torch.int32), row_map=z(n * B, dt=torch.int32), conf=z(n * B),
              argmax=z(n * B, dt=torch.int32), hidden_full=z(n * B, h), hidden_packed=z(n * B, h), logits=z(n * B, V))
     if wl.n_experts:
@@ -141,6 +141,7 @@ def compare_sample(wl, g, b, i, tr, tf, exp_k, label):
     B = wl.block_size
     rows = g["rows"][b]
     assert relerr(g["importance"][b], tr.I_evict[i]) <= TOL
+    assert relerr(g["importance_prev"][b], tr.I_prev[i]) <= TOL
     scale = float(np.max(np.abs(tr.delta_I[i])))
     assert float(np.max(np.abs(g["delta_I"][b] - tr.delta_I[i]))) <= 2 * TOL * float(np.max(np.abs(tr.I_evict[i])))
     masked = [bool((g["mask_before"][b] >> p) & 1) for p in range(B)]

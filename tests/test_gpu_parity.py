@@ -146,6 +146,9 @@ def compare_steps(wl, steps, tol, exact, seq_ids=None, k_override=None, forced_r
         # bounded on that scale (relative to the delta's own size it can be anything when the two layers nearly agree)
         a_dI = max(float(np.max(np.abs(g["delta_I"][b] - tr.delta_I[b]))) / max(float(np.max(np.abs(tr.I_evict[b]))), 1e-30) for b in range(n))
         assert e_I <= tol and a_dI <= 2 * tol, (e_I, a_dI, e_dI)
+        if tr.I_prev:           # Eq. 2 of the layer below the eviction layer (computed inside that layer's attention launch where possible)
+            e_Ip = max(relerr(g["importance_prev"][b], tr.I_prev[b]) for b in range(n))
+            assert e_Ip <= tol, e_Ip
         for b in range(n):      # Eq. 2 sums to (query rows) x H_q: all B positions, or those not frozen (Sec. 4.3)
             assert abs(float(g["importance"][b].sum()) - len(tr.uncached[b]) * wl.n_q_heads) < 1e-2 * B * wl.n_q_heads * tol + 1e-3
         # decisions
